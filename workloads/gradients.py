@@ -21,15 +21,19 @@ import numpy as np
 _SIGMA_STREAM = 0xFFFFFFFF
 
 
+def _key(seed: int, worker: int, tensor: int) -> np.ndarray:
+    return np.array([seed, (worker << 32) | tensor], dtype=np.uint64)
+
+
 def sigma(seed: int, tensor: int) -> np.float32:
-    g = np.random.Generator(np.random.Philox(key=[seed, (_SIGMA_STREAM << 32) | tensor]))
+    g = np.random.Generator(np.random.Philox(key=_key(seed, _SIGMA_STREAM, tensor)))
     u = g.random()
     return np.float32(10.0 ** (-4.0 + 3.0 * u))
 
 
 def tensor_values(seed: int, worker: int, tensor: int, n: int, bf16: bool = False) -> np.ndarray:
     """Values of one tensor of one replica: float32[n], or uint16[n] bf16 bit patterns."""
-    g = np.random.Generator(np.random.Philox(key=[seed, (worker << 32) | tensor]))
+    g = np.random.Generator(np.random.Philox(key=_key(seed, worker, tensor)))
     x = g.standard_normal(n, dtype=np.float32)
     x *= sigma(seed, tensor)
     if bf16:
