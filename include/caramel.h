@@ -1,0 +1,215 @@
+/* caramel.h -- C ABI of the Caramel aggregation hot path for MI355X (gfx950).
+ *
+ * What the library computes.  W workers ("replicas") each hold a gradient for
+ * every parameter of a model, of the same byte length at every worker, and the
+ * aggregate is their sum (paper section 2); here the W replicas are resident
+ * in the memory of ONE GPU and the result is their average, written back into
+ * every replica.  The work is organised the way Caramel organises AllReduce
+ * traffic:
+ *
+ *   - small parameters are batched into fused transfers (section 4.2,
+ *     "Parameter Batcher"): walking the parameters in update order, one whose
+ *     size reaches the threshold is transferred on its own, a smaller one
+ *     joins the open batch, and the batch is sent once it has reached the
+ *     threshold;
+ *   - large transfers are cut into `depth` chunks that are aggregated
+ *     independently and in parallel (section 4.4, "Adaptive Depth Enforcer");
+ *   - every transfer unit (batch or chunk) is aggregated with the ring/bucket
+ *     pattern (sections 2 and 4.4): the unit is cut into W segments, the
+ *     partial sum of segment c starts at worker c+1, is added to at each
+ *     worker round the ring and completes at worker c, which scales it by 1/W;
+ *     the result is then copied to all workers.  Sums are fp32, in exactly that
+ *     order, so results are reproducible bit for bit.
+ *
+ * Memory.  All `void*` data arguments named "device" are device pointers;
+ * everything else is host memory.  The caller owns gradients and workspace and
+ * must keep them alive until the stream work has completed.  The library
+ * allocates only its own small descriptor tables (at caramel_bind).
+ *
+ * Errors.  Every function returns a status; nothing throws across the ABI.  On
+ * a non-zero status nothing has been launched unless stated, and
+ * caramel_last_error() describes the failure.
+ *
+ * Threads.  A plan may be used by one host thread at a time.
+ */
+#ifndef CARAMEL_H
+#define CARAMEL_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+enum { CARAMEL_OK = 0, CARAMEL_EINVAL = 1, CARAMEL_ENOMEM = 2, CARAMEL_EHIP = 3, CARAMEL_ESTATE = 4 };
+enum { CARAMEL_F32 = 0, CARAMEL_BF16 = 1 };
+enum { CARAMEL_SPLIT_NONE = 0, CARAMEL_SPLIT_FIXED = 1, CARAMEL_SPLIT_ADAPTIVE = 2 };
+enum { CARAMEL_KIND_BATCH = 0, CARAMEL_KIND_CHUNK = 1 };
+
+/* Plan parameters.
+ *   world                 W >= 1 replicas (at most CARAMEL_MAX_WORLD).
+ *   dtype                 element type of gradients and results.  BF16: inputs are widened
+ *                         exactly, partial sums stay fp32 through all ring hops, one
+ *                         round-to-nearest-even on output.
+ *   batch_threshold_bytes T of section 4.2; a tensor of >= T bytes is "large".  0 switches
+ *                         batching off (every tensor is its own transfer).
+ *   split_mode            section 4.4.  NONE: depth 1.  FIXED: chunks of exactly split_bytes
+ *                         (last one shorter), any count.  ADAPTIVE: depth =
+ *                         clamp(floor(bytes / split_bytes), 1, max_depth), equal chunks
+ *                         rounded up to whole granules; the paper's setting is split_bytes = T,
+ *                         max_depth = 8.
+ *   align_bytes           granule: batch members and ring segments start on multiples of it.
+ *                         A power of two, >= 16 (one 128-bit vector).
+ *   num_streams           1 or 2 internal streams; unit u runs on stream u mod num_streams.
+ */
+typedef struct caramel_config {
+  uint32_t world;
+  uint32_t dtype;
+  uint64_t batch_threshold_bytes;
+  uint32_t split_mode;
+  uint32_t max_depth;
+  uint64_t split_bytes;
+  uint32_t align_bytes;
+  uint32_t num_streams;
+} caramel_config;
+
+#define CARAMEL_MAX_WORLD 64u
+
+/* One transfer unit, in queue (emission) order. */
+typedef struct caramel_unit {
+  uint32_t kind;        /* CARAMEL_KIND_BATCH or CARAMEL_KIND_CHUNK */
+  uint32_t stream;      /* unit index mod num_streams */
+  uint32_t first_entry; /* entries [first_entry, first_entry + n_entries) belong to this unit */
+  uint32_t n_entries;   /* chunk: 1 */
+  uint64_t elems;       /* batch: padded to whole granules; chunk: exact */
+  uint64_t fused_off;   /* batch: element offset in each replica's fused buffer; chunk: 0 */
+} caramel_unit;
+
+/* One contiguous piece of one tensor inside one unit.  Entries are grouped by unit. */
+typedef struct caramel_entry {
+  uint32_t tensor;      /* index into the tensor list given to caramel_plan_create */
+  uint32_t unit;
+  uint64_t tensor_off;  /* first element of the tensor covered */
+  uint64_t unit_off;    /* element offset inside the unit (multiple of the granule) */
+  uint64_t elems;
+} caramel_entry;
+
+typedef struct caramel_plan caramel_plan; /* opaque, owned by the library */
+
+/* ---- planning: host only, deterministic, no GPU needed (sections 4.2, 4.4) ------------- */
+
+/* Build the plan for `n_tensors` tensors with the given element counts, listed in update
+ * order (ascending expected update time, section 4.2).  *out receives a new plan.
+ * EINVAL: NULL argument, n_tensors == 0, a zero-element tensor, world out of range, unknown
+ * dtype or split mode, align_bytes not a power of two >= 16, split_bytes not a positive
+ * multiple of align_bytes when splitting, num_streams not 1 or 2, max_depth == 0 (ADAPTIVE). */
+int caramel_plan_create(const caramel_config* cfg, const uint64_t* tensor_elems, uint32_t n_tensors,
+                        caramel_plan** out);
+
+/* Free host and device tables and internal streams/events.  NULL is allowed. */
+void caramel_plan_destroy(caramel_plan* plan);
+
+/* Introspection.  Any out pointer may be NULL. */
+int caramel_plan_counts(const caramel_plan* plan, uint32_t* n_units, uint32_t* n_entries,
+                        uint64_t* fused_elems);
+/* Copy up to `cap` records; EINVAL if cap is smaller than the count. */
+int caramel_plan_units(const caramel_plan* plan, caramel_unit* out, uint32_t cap);
+int caramel_plan_entries(const caramel_plan* plan, caramel_entry* out, uint32_t cap);
+/* Ring segments of one unit: world+1 element offsets; segment c = [seg[c], seg[c+1]) is the
+ * part whose sum completes at worker c. */
+int caramel_plan_segments(const caramel_plan* plan, uint32_t unit, uint64_t* seg_start);
+/* Canonical little-endian image of the plan (config, units, entries, segments).  Call with
+ * buf == NULL to get the size in *len; otherwise *len is the capacity on entry and the size
+ * written on return (EINVAL if too small). */
+int caramel_plan_serialize(const caramel_plan* plan, void* buf, size_t* len);
+
+/* ---- execution on the GPU ---------------------------------------------------------------- */
+
+/* Attach memory to a plan.
+ *   grads     host array of world * n_tensors DEVICE pointers; grads[w * n_tensors + t] is
+ *             worker w's tensor t (tensor_elems[t] elements of the plan's dtype), aligned to
+ *             align_bytes.  Replicas must not overlap.
+ *   fused_ws  DEVICE workspace of world * fused_elems elements (replica w's fused buffer starts
+ *             at element w * fused_elems); may be NULL when fused_elems == 0, or when only
+ *             caramel_allreduce in its default (direct) mode is going to be used.
+ * The library uploads its descriptor tables (synchronously) and creates its internal streams.
+ * May be called again to re-bind.  EINVAL: NULL/misaligned pointer.  EHIP: a HIP call failed. */
+int caramel_bind(caramel_plan* plan, void* const* grads, void* fused_ws);
+
+/* `stream` is a hipStream_t handle (NULL = the default stream).  All four calls are
+ * asynchronous: work is ordered after what is already queued on `stream`, and later work on
+ * `stream` is ordered after it.  ESTATE: plan not bound (or no workspace where one is needed).
+ *
+ * caramel_pack         batch units: every member tensor of every replica -> fused_ws at its
+ *                      planned offset; alignment padding is written as +0.0 (section 4.2).
+ * caramel_ring_reduce  every unit, in place: batch units in fused_ws, chunk units directly in
+ *                      tensor memory.  Ring reduce-scatter order, scale by 1/W, all-gather to
+ *                      all W replicas (sections 2, 4.4).  Units run on the plan's internal
+ *                      streams (unit u on stream u mod num_streams) between a fork from and a
+ *                      join back to `stream`, both with events.
+ * caramel_unpack       batch units: fused_ws -> member tensors of every replica.
+ * caramel_allreduce    the whole path; afterwards every grads[w][t] holds the average, the same
+ *                      bytes for every w, and identical to pack -> ring_reduce -> unpack.
+ */
+int caramel_pack(caramel_plan* plan, void* stream);
+int caramel_ring_reduce(caramel_plan* plan, void* stream);
+int caramel_unpack(caramel_plan* plan, void* stream);
+int caramel_allreduce(caramel_plan* plan, void* stream);
+
+/* ---- launch tuning and timing (do not change results) ------------------------------------ */
+
+enum {
+  /* How units map to kernel launches.  PER_UNIT: one launch per unit and stage (the literal
+   * pipeline).  PER_STREAM: consecutive units of one internal stream share launches through a
+   * descriptor table.  Default PER_STREAM. */
+  CARAMEL_OPT_LAUNCH_MODE = 0,
+  /* Batch units in caramel_allreduce.  STAGED: pack -> reduce -> unpack through fused_ws.
+   * DIRECT: one gather-reduce-scatter kernel that reads member tensors and writes results back
+   * without materialising the fused buffer (same segments, same order, same bits).
+   * Default DIRECT. */
+  CARAMEL_OPT_BATCH_PATH = 1,
+  /* 16-byte vectors per replica handled by one workgroup tile of the reduce kernel. */
+  CARAMEL_OPT_TILE_VECS = 2,
+  /* Upper bound on workgroups per reduce launch (0 = one workgroup per tile). */
+  CARAMEL_OPT_MAX_GRID = 3,
+  /* Non-zero: streaming (non-temporal) loads/stores in the reduce kernel. */
+  CARAMEL_OPT_NONTEMPORAL = 4,
+  /* 16-byte vectors each lane keeps in flight per worker: 1, 2 or 4; 0 = chosen from W. */
+  CARAMEL_OPT_UNROLL = 5
+};
+enum { CARAMEL_LAUNCH_PER_UNIT = 0, CARAMEL_LAUNCH_PER_STREAM = 1 };
+enum { CARAMEL_BATCH_STAGED = 0, CARAMEL_BATCH_DIRECT = 1 };
+
+/* Set a launch option; takes effect at the next caramel_bind (tables are rebuilt there).
+ * EINVAL for an unknown option or a value out of range. */
+int caramel_plan_set_option(caramel_plan* plan, uint32_t option, uint64_t value);
+
+enum { CARAMEL_K_PACK = 0, CARAMEL_K_REDUCE = 1, CARAMEL_K_UNPACK = 2, CARAMEL_K_COUNT = 3 };
+
+/* Per-kernel timing, measured with HIP events recorded on the stream each kernel is launched
+ * on.  `launches`/`total_ms` accumulate over calls since profiling was switched on; `span_ms`
+ * accumulates, per call, the time from the earliest start to the latest end of that kernel's
+ * launches (launches on the two internal streams overlap, so span <= total). */
+typedef struct caramel_kernel_stat {
+  uint64_t launches;
+  double total_ms;
+  double span_ms;
+  uint64_t calls;
+} caramel_kernel_stat;
+
+/* Switch event timing on (non-zero) or off and clear the statistics.  Requires a bound plan. */
+int caramel_profile(caramel_plan* plan, int enable);
+/* Synchronise the internal streams, fold pending event pairs into the statistics and copy
+ * CARAMEL_K_COUNT records to `out`. */
+int caramel_profile_read(caramel_plan* plan, caramel_kernel_stat* out);
+
+/* Message for the calling thread's last non-OK status ("" if none). */
+const char* caramel_last_error(void);
+/* Library version, major * 10000 + minor * 100 + patch. */
+int caramel_version(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* CARAMEL_H */

@@ -1,0 +1,75 @@
+"""MI355X-native implementation of the hot path of Caramel's AllReduce aggregation.
+
+The work is done by hand-written HIP kernels behind the C ABI declared in
+include/caramel.h; this package only marshals arguments (binding.py) and, in
+device.py, uses PyTorch to hold device memory and streams.
+"""
+from .binding import (BATCH_DIRECT, BATCH_STAGED, BF16, F32, K_COUNT, K_PACK, K_REDUCE, K_UNPACK,
+                      KIND_BATCH, KIND_CHUNK, LAUNCH_PER_STREAM, LAUNCH_PER_UNIT, OPT_BATCH_PATH,
+                      OPT_LAUNCH_MODE, OPT_MAX_GRID, OPT_NONTEMPORAL, OPT_TILE_VECS, OPT_UNROLL,
+                      SPLIT_ADAPTIVE, SPLIT_FIXED, SPLIT_NONE, CaramelError, Config, Entry, Plan, Unit, lib)
+
+
+# Functional spellings with the names of the C entry points.
+def caramel_plan_create(world, elems, **kw) -> Plan:
+    return Plan(world, elems, **kw)
+
+
+def caramel_plan_destroy(plan: Plan) -> None:
+    plan.close()
+
+
+def caramel_plan_counts(plan: Plan):
+    return plan.counts()
+
+
+def caramel_plan_units(plan: Plan):
+    return plan.units()
+
+
+def caramel_plan_entries(plan: Plan):
+    return plan.entries()
+
+
+def caramel_plan_segments(plan: Plan, unit: int):
+    return plan.segments(unit)
+
+
+def caramel_plan_serialize(plan: Plan) -> bytes:
+    return plan.serialize()
+
+
+def caramel_plan_set_option(plan: Plan, option: int, value: int) -> None:
+    plan.set_option(option, value)
+
+
+def caramel_bind(plan: Plan, grad_ptrs, fused_ws) -> None:
+    plan.bind(grad_ptrs, fused_ws)
+
+
+def caramel_pack(plan: Plan, stream: int = 0) -> None:
+    plan.pack(stream)
+
+
+def caramel_ring_reduce(plan: Plan, stream: int = 0) -> None:
+    plan.ring_reduce(stream)
+
+
+def caramel_unpack(plan: Plan, stream: int = 0) -> None:
+    plan.unpack(stream)
+
+
+def caramel_allreduce(plan: Plan, stream: int = 0) -> None:
+    plan.allreduce(stream)
+
+
+def caramel_profile(plan: Plan, enable: bool) -> None:
+    plan.profile(enable)
+
+
+def caramel_profile_read(plan: Plan):
+    return plan.profile_read()
+
+
+def caramel_version() -> int:
+    return lib().caramel_version()

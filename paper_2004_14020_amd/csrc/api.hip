@@ -1,0 +1,513 @@
+// C ABI of the library: plan objects, binding of device memory, stream pipeline, timing.
+#include <hip/hip_runtime.h>
+
+#include <algorithm>
+#include <cstdarg>
+#include <cstdio>
+#include <cstring>
+#include <new>
+#include <string>
+#include <vector>
+
+#include "caramel.h"
+#include "kernels.hpp"
+#include "plan.hpp"
+#include "tiles.hpp"
+
+using namespace caramel;
+
+namespace {
+
+thread_local std::string g_err;
+
+int fail(int code, const char* fmt, ...) {
+  char buf[512];
+  va_list ap;
+  va_start(ap, fmt);
+  vsnprintf(buf, sizeof buf, fmt, ap);
+  va_end(ap);
+  g_err = buf;
+  return code;
+}
+
+#define HIP_TRY(expr)                                                                         \
+  do {                                                                                        \
+    hipError_t e_ = (expr);                                                                   \
+    if (e_ != hipSuccess) return fail(CARAMEL_EHIP, "%s: %s", #expr, hipGetErrorString(e_)); \
+  } while (0)
+
+struct Options {
+  uint32_t launch_mode = CARAMEL_LAUNCH_PER_STREAM;
+  uint32_t batch_path = CARAMEL_BATCH_DIRECT;
+  uint32_t tile_vecs = 1024;
+  uint32_t copy_vecs = 512;
+  uint32_t max_grid = 0;
+  uint32_t nontemporal = 1;
+  uint32_t unroll = 0;
+};
+
+struct TimedLaunch {
+  int kind;
+  uint64_t call;
+  hipEvent_t start, stop;
+};
+
+}  // namespace
+
+struct caramel_plan {
+  HostPlan host;
+  Options opt;
+  // device side (valid when bound)
+  bool bound = false;
+  bool has_ws = false;
+  TileTables tt;
+  uint64_t* d_rows = nullptr;
+  ReduceTile* d_staged = nullptr;
+  ReduceTile* d_direct = nullptr;
+  CopyTile* d_copy = nullptr;
+  hipStream_t streams[2] = {nullptr, nullptr};
+  hipEvent_t ev_fork = nullptr;
+  hipEvent_t ev_join[2] = {nullptr, nullptr};
+  // timing
+  bool profiling = false;
+  uint64_t call_no = 0;
+  std::vector<TimedLaunch> pending;
+  std::vector<hipEvent_t> spare;
+  std::vector<std::pair<uint64_t, hipEvent_t>> call_base;
+  caramel_kernel_stat stats[CARAMEL_K_COUNT] = {};
+};
+
+namespace {
+
+void release_device(caramel_plan* p) {
+  if (p->d_rows) (void)hipFree(p->d_rows);
+  if (p->d_staged) (void)hipFree(p->d_staged);
+  if (p->d_direct) (void)hipFree(p->d_direct);
+  if (p->d_copy) (void)hipFree(p->d_copy);
+  p->d_rows = nullptr;
+  p->d_staged = p->d_direct = nullptr;
+  p->d_copy = nullptr;
+  p->bound = false;
+}
+
+void drop_events(caramel_plan* p) {
+  for (TimedLaunch& t : p->pending) {
+    (void)hipEventDestroy(t.start);
+    (void)hipEventDestroy(t.stop);
+  }
+  for (auto& b : p->call_base) (void)hipEventDestroy(b.second);
+  for (hipEvent_t e : p->spare) (void)hipEventDestroy(e);
+  p->pending.clear();
+  p->call_base.clear();
+  p->spare.clear();
+}
+
+template <typename T>
+int upload(const std::vector<T>& v, T** dst) {
+  *dst = nullptr;
+  if (v.empty()) return CARAMEL_OK;
+  HIP_TRY(hipMalloc(reinterpret_cast<void**>(dst), v.size() * sizeof(T)));
+  HIP_TRY(hipMemcpy(*dst, v.data(), v.size() * sizeof(T), hipMemcpyHostToDevice));
+  return CARAMEL_OK;
+}
+
+hipEvent_t take_event(caramel_plan* p) {
+  if (!p->spare.empty()) {
+    hipEvent_t e = p->spare.back();
+    p->spare.pop_back();
+    return e;
+  }
+  hipEvent_t e = nullptr;
+  if (hipEventCreate(&e) != hipSuccess) return nullptr;
+  return e;
+}
+
+// Wraps one kernel launch in a pair of timing events on the launch stream when profiling.
+struct Timed {
+  caramel_plan* p;
+  hipStream_t s;
+  TimedLaunch t{};
+  bool on = false;
+  Timed(caramel_plan* plan, int kind, hipStream_t stream) : p(plan), s(stream) {
+    if (!p->profiling) return;
+    t.kind = kind;
+    t.call = p->call_no;
+    t.start = take_event(p);
+    t.stop = take_event(p);
+    if (!t.start || !t.stop) return;
+    on = hipEventRecord(t.start, s) == hipSuccess;
+  }
+  ~Timed() {
+    if (!on) return;
+    (void)hipEventRecord(t.stop, s);
+    p->pending.push_back(t);
+  }
+};
+
+int run_reduce(caramel_plan* p, bool direct, Range r, hipStream_t s) {
+  if (r.count == 0) return CARAMEL_OK;
+  ReduceArgs a{};
+  a.tiles = direct ? p->d_direct : p->d_staged;
+  a.rows = p->d_rows;
+  a.begin = r.begin;
+  a.count = r.count;
+  a.world = p->host.cfg.world;
+  a.bf16 = p->host.cfg.dtype == CARAMEL_BF16;
+  a.nontemporal = p->opt.nontemporal != 0;
+  a.unroll = p->opt.unroll;
+  a.max_grid = p->opt.max_grid;
+  Timed timer(p, CARAMEL_K_REDUCE, s);
+  HIP_TRY(launch_ring_reduce(a, s));
+  return CARAMEL_OK;
+}
+
+int run_copy(caramel_plan* p, bool unpack, Range r, hipStream_t s) {
+  if (r.count == 0) return CARAMEL_OK;
+  CopyArgs a{};
+  a.tiles = p->d_copy;
+  a.rows = p->d_rows;
+  a.begin = r.begin;
+  a.count = r.count;
+  a.world = p->host.cfg.world;
+  a.fused_row = uint32_t(p->host.tensor_elems.size());
+  a.bf16 = p->host.cfg.dtype == CARAMEL_BF16;
+  a.unpack = unpack;
+  Timed timer(p, unpack ? CARAMEL_K_UNPACK : CARAMEL_K_PACK, s);
+  HIP_TRY(launch_copy(a, s));
+  return CARAMEL_OK;
+}
+
+int begin_call(caramel_plan* p, hipStream_t user) {
+  ++p->call_no;
+  if (p->profiling) {
+    hipEvent_t e = take_event(p);
+    if (e && hipEventRecord(e, user) == hipSuccess) p->call_base.emplace_back(p->call_no, e);
+  }
+  return CARAMEL_OK;
+}
+
+// Internal streams start after everything queued on the caller's stream ...
+int fork_streams(caramel_plan* p, hipStream_t user, hipStream_t* lane) {
+  const uint32_t ns = p->host.cfg.num_streams;
+  if (ns == 1) {
+    lane[0] = user;
+    return CARAMEL_OK;
+  }
+  HIP_TRY(hipEventRecord(p->ev_fork, user));
+  for (uint32_t s = 0; s < ns; ++s) {
+    HIP_TRY(hipStreamWaitEvent(p->streams[s], p->ev_fork, 0));
+    lane[s] = p->streams[s];
+  }
+  return CARAMEL_OK;
+}
+
+// ... and the caller's stream continues after both have drained.
+int join_streams(caramel_plan* p, hipStream_t user) {
+  const uint32_t ns = p->host.cfg.num_streams;
+  if (ns == 1) return CARAMEL_OK;
+  for (uint32_t s = 0; s < ns; ++s) {
+    HIP_TRY(hipEventRecord(p->ev_join[s], p->streams[s]));
+    HIP_TRY(hipStreamWaitEvent(user, p->ev_join[s], 0));
+  }
+  return CARAMEL_OK;
+}
+
+// Shared body of caramel_ring_reduce (reduce only, staged tables) and caramel_allreduce.
+int pipeline(caramel_plan* p, hipStream_t user, bool with_copies, bool direct) {
+  begin_call(p, user);
+  hipStream_t lane[2] = {nullptr, nullptr};
+  int rc = fork_streams(p, user, lane);
+  if (rc) return rc;
+  const TileTables& tt = p->tt;
+  const std::vector<Range>& unit_tiles = direct ? tt.direct_unit : tt.staged_unit;
+  const Range* stream_tiles = direct ? tt.direct_stream : tt.staged_stream;
+  const bool copies = with_copies && !direct;
+  if (p->opt.launch_mode == CARAMEL_LAUNCH_PER_STREAM) {
+    for (uint32_t s = 0; s < p->host.cfg.num_streams && !rc; ++s) {
+      if (copies) rc = run_copy(p, false, tt.copy_stream[s], lane[s]);
+      if (!rc) rc = run_reduce(p, direct, stream_tiles[s], lane[s]);
+      if (!rc && copies) rc = run_copy(p, true, tt.copy_stream[s], lane[s]);
+    }
+  } else {
+    for (uint32_t u = 0; u < p->host.units.size() && !rc; ++u) {
+      hipStream_t s = lane[p->host.units[u].stream];
+      if (copies) rc = run_copy(p, false, tt.copy_unit[u], s);
+      if (!rc) rc = run_reduce(p, direct, unit_tiles[u], s);
+      if (!rc && copies) rc = run_copy(p, true, tt.copy_unit[u], s);
+    }
+  }
+  // join even after a failed launch so the caller's stream stays ordered
+  const int jc = join_streams(p, user);
+  return rc ? rc : jc;
+}
+
+int need_bound(const caramel_plan* p, bool needs_ws) {
+  if (!p) return fail(CARAMEL_EINVAL, "plan is NULL");
+  if (!p->bound) return fail(CARAMEL_ESTATE, "plan is not bound to device memory");
+  if (needs_ws && p->host.fused_elems > 0 && !p->has_ws)
+    return fail(CARAMEL_ESTATE, "this call needs the fused workspace, but none was bound");
+  return CARAMEL_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+int caramel_plan_create(const caramel_config* cfg, const uint64_t* tensor_elems, uint32_t n_tensors,
+                        caramel_plan** out) {
+  if (!cfg || !out) return fail(CARAMEL_EINVAL, "NULL argument");
+  *out = nullptr;
+  caramel_plan* p = new (std::nothrow) caramel_plan;
+  if (!p) return fail(CARAMEL_ENOMEM, "out of host memory");
+  std::string why;
+  int rc;
+  try {
+    rc = build_host_plan(*cfg, tensor_elems, n_tensors, p->host, why);
+  } catch (const std::bad_alloc&) {
+    delete p;
+    return fail(CARAMEL_ENOMEM, "out of host memory");
+  }
+  if (rc != CARAMEL_OK) {
+    delete p;
+    return fail(rc, "%s", why.c_str());
+  }
+  *out = p;
+  return CARAMEL_OK;
+}
+
+void caramel_plan_destroy(caramel_plan* p) {
+  if (!p) return;
+  if (p->bound || p->streams[0] || p->ev_fork) {
+    for (int s = 0; s < 2; ++s)
+      if (p->streams[s]) (void)hipStreamSynchronize(p->streams[s]);
+    drop_events(p);
+    release_device(p);
+    for (int s = 0; s < 2; ++s) {
+      if (p->streams[s]) (void)hipStreamDestroy(p->streams[s]);
+      if (p->ev_join[s]) (void)hipEventDestroy(p->ev_join[s]);
+    }
+    if (p->ev_fork) (void)hipEventDestroy(p->ev_fork);
+  }
+  delete p;
+}
+
+int caramel_plan_counts(const caramel_plan* p, uint32_t* n_units, uint32_t* n_entries, uint64_t* fused_elems) {
+  if (!p) return fail(CARAMEL_EINVAL, "plan is NULL");
+  if (n_units) *n_units = uint32_t(p->host.units.size());
+  if (n_entries) *n_entries = uint32_t(p->host.entries.size());
+  if (fused_elems) *fused_elems = p->host.fused_elems;
+  return CARAMEL_OK;
+}
+
+int caramel_plan_units(const caramel_plan* p, caramel_unit* out, uint32_t cap) {
+  if (!p || !out) return fail(CARAMEL_EINVAL, "NULL argument");
+  if (cap < p->host.units.size()) return fail(CARAMEL_EINVAL, "capacity %u < %zu units", cap, p->host.units.size());
+  std::copy(p->host.units.begin(), p->host.units.end(), out);
+  return CARAMEL_OK;
+}
+
+int caramel_plan_entries(const caramel_plan* p, caramel_entry* out, uint32_t cap) {
+  if (!p || !out) return fail(CARAMEL_EINVAL, "NULL argument");
+  if (cap < p->host.entries.size())
+    return fail(CARAMEL_EINVAL, "capacity %u < %zu entries", cap, p->host.entries.size());
+  std::copy(p->host.entries.begin(), p->host.entries.end(), out);
+  return CARAMEL_OK;
+}
+
+int caramel_plan_segments(const caramel_plan* p, uint32_t unit, uint64_t* seg_start) {
+  if (!p || !seg_start) return fail(CARAMEL_EINVAL, "NULL argument");
+  if (unit >= p->host.units.size()) return fail(CARAMEL_EINVAL, "unit %u out of range", unit);
+  const uint64_t* s = p->host.segments(unit);
+  std::copy(s, s + p->host.cfg.world + 1, seg_start);
+  return CARAMEL_OK;
+}
+
+int caramel_plan_serialize(const caramel_plan* p, void* buf, size_t* len) {
+  if (!p || !len) return fail(CARAMEL_EINVAL, "NULL argument");
+  const std::vector<uint8_t> img = serialize(p->host);
+  if (!buf) {
+    *len = img.size();
+    return CARAMEL_OK;
+  }
+  if (*len < img.size()) return fail(CARAMEL_EINVAL, "buffer of %zu bytes, need %zu", *len, img.size());
+  std::memcpy(buf, img.data(), img.size());
+  *len = img.size();
+  return CARAMEL_OK;
+}
+
+int caramel_plan_set_option(caramel_plan* p, uint32_t option, uint64_t value) {
+  if (!p) return fail(CARAMEL_EINVAL, "plan is NULL");
+  switch (option) {
+    case CARAMEL_OPT_LAUNCH_MODE:
+      if (value > CARAMEL_LAUNCH_PER_STREAM) return fail(CARAMEL_EINVAL, "unknown launch mode");
+      p->opt.launch_mode = uint32_t(value);
+      return CARAMEL_OK;
+    case CARAMEL_OPT_BATCH_PATH:
+      if (value > CARAMEL_BATCH_DIRECT) return fail(CARAMEL_EINVAL, "unknown batch path");
+      p->opt.batch_path = uint32_t(value);
+      return CARAMEL_OK;
+    case CARAMEL_OPT_TILE_VECS:
+      if (value < 64 || value > (1u << 20)) return fail(CARAMEL_EINVAL, "tile_vecs must be in [64, 2^20]");
+      p->opt.tile_vecs = uint32_t(value);
+      return CARAMEL_OK;
+    case CARAMEL_OPT_MAX_GRID:
+      if (value > 0x7FFFFFFFu) return fail(CARAMEL_EINVAL, "max_grid too large");
+      p->opt.max_grid = uint32_t(value);
+      return CARAMEL_OK;
+    case CARAMEL_OPT_NONTEMPORAL:
+      p->opt.nontemporal = value ? 1 : 0;
+      return CARAMEL_OK;
+    case CARAMEL_OPT_UNROLL:
+      if (value != 0 && value != 1 && value != 2 && value != 4) return fail(CARAMEL_EINVAL, "unroll must be 0, 1, 2 or 4");
+      p->opt.unroll = uint32_t(value);
+      return CARAMEL_OK;
+    default:
+      return fail(CARAMEL_EINVAL, "unknown option %u", option);
+  }
+}
+
+int caramel_bind(caramel_plan* p, void* const* grads, void* fused_ws) {
+  if (!p || !grads) return fail(CARAMEL_EINVAL, "NULL argument");
+  const HostPlan& h = p->host;
+  const uint32_t W = h.cfg.world;
+  const size_t n = h.tensor_elems.size();
+  const uint64_t es = h.elem_size();
+  // argument checks first: nothing is touched on the device if they fail
+  struct Span {
+    uint64_t lo, hi;
+  };
+  std::vector<Span> spans;
+  spans.reserve(W * n + 1);
+  for (uint32_t w = 0; w < W; ++w)
+    for (size_t t = 0; t < n; ++t) {
+      const uint64_t a = reinterpret_cast<uint64_t>(grads[w * n + t]);
+      if (a == 0) return fail(CARAMEL_EINVAL, "grads[%u][%zu] is NULL", w, t);
+      if (a % h.cfg.align_bytes) return fail(CARAMEL_EINVAL, "grads[%u][%zu] is not aligned to %u bytes", w, t, h.cfg.align_bytes);
+      spans.push_back({a, a + h.tensor_elems[t] * es});
+    }
+  if (fused_ws) {
+    const uint64_t a = reinterpret_cast<uint64_t>(fused_ws);
+    if (a % h.cfg.align_bytes) return fail(CARAMEL_EINVAL, "fused_ws is not aligned to %u bytes", h.cfg.align_bytes);
+    if (h.fused_elems) spans.push_back({a, a + uint64_t(W) * h.fused_elems * es});
+  }
+  std::sort(spans.begin(), spans.end(), [](const Span& x, const Span& y) { return x.lo < y.lo; });
+  for (size_t i = 1; i < spans.size(); ++i)
+    if (spans[i].lo < spans[i - 1].hi) return fail(CARAMEL_EINVAL, "gradient / workspace buffers overlap");
+
+  for (int s = 0; s < 2; ++s)
+    if (p->streams[s]) HIP_TRY(hipStreamSynchronize(p->streams[s]));
+  release_device(p);
+
+  build_tiles(h, p->opt.tile_vecs, p->opt.copy_vecs, p->tt);
+  std::vector<uint64_t> rows((n + 1) * W, 0);
+  for (uint32_t w = 0; w < W; ++w) {
+    for (size_t t = 0; t < n; ++t) rows[t * W + w] = reinterpret_cast<uint64_t>(grads[w * n + t]);
+    rows[n * W + w] = fused_ws ? reinterpret_cast<uint64_t>(fused_ws) + uint64_t(w) * h.fused_elems * es : 0;
+  }
+  int rc = upload(rows, &p->d_rows);
+  if (!rc) rc = upload(p->tt.direct, &p->d_direct);
+  if (!rc && fused_ws) rc = upload(p->tt.staged, &p->d_staged);
+  if (!rc && fused_ws) rc = upload(p->tt.copy, &p->d_copy);
+  if (rc) {
+    release_device(p);
+    return rc;
+  }
+  if (h.cfg.num_streams > 1 && !p->streams[0]) {
+    for (uint32_t s = 0; s < h.cfg.num_streams; ++s) {
+      HIP_TRY(hipStreamCreateWithFlags(&p->streams[s], hipStreamNonBlocking));
+      HIP_TRY(hipEventCreateWithFlags(&p->ev_join[s], hipEventDisableTiming));
+    }
+    HIP_TRY(hipEventCreateWithFlags(&p->ev_fork, hipEventDisableTiming));
+  }
+  p->has_ws = fused_ws != nullptr;
+  p->bound = true;
+  return CARAMEL_OK;
+}
+
+int caramel_pack(caramel_plan* p, void* stream) {
+  if (int rc = need_bound(p, true)) return rc;
+  begin_call(p, hipStream_t(stream));
+  Range all{0, uint32_t(p->tt.copy.size())};
+  return run_copy(p, false, all, hipStream_t(stream));
+}
+
+int caramel_unpack(caramel_plan* p, void* stream) {
+  if (int rc = need_bound(p, true)) return rc;
+  begin_call(p, hipStream_t(stream));
+  Range all{0, uint32_t(p->tt.copy.size())};
+  return run_copy(p, true, all, hipStream_t(stream));
+}
+
+int caramel_ring_reduce(caramel_plan* p, void* stream) {
+  if (int rc = need_bound(p, true)) return rc;
+  // without a workspace there are no batch units, and the two tables coincide
+  return pipeline(p, hipStream_t(stream), false, !p->has_ws);
+}
+
+int caramel_allreduce(caramel_plan* p, void* stream) {
+  const bool direct = p && (p->opt.batch_path == CARAMEL_BATCH_DIRECT || p->host.fused_elems == 0);
+  if (int rc = need_bound(p, !direct)) return rc;
+  return pipeline(p, hipStream_t(stream), true, direct);
+}
+
+int caramel_profile(caramel_plan* p, int enable) {
+  if (int rc = need_bound(p, false)) return rc;
+  for (int s = 0; s < 2; ++s)
+    if (p->streams[s]) HIP_TRY(hipStreamSynchronize(p->streams[s]));
+  drop_events(p);
+  std::memset(p->stats, 0, sizeof p->stats);
+  p->profiling = enable != 0;
+  return CARAMEL_OK;
+}
+
+int caramel_profile_read(caramel_plan* p, caramel_kernel_stat* out) {
+  if (int rc = need_bound(p, false)) return rc;
+  if (!out) return fail(CARAMEL_EINVAL, "out is NULL");
+  // every pending stop event has completed once its own synchronize returns
+  struct Window {
+    float lo, hi;
+    bool any;
+  };
+  size_t bi = 0;
+  for (size_t i = 0; i < p->pending.size();) {
+    const uint64_t call = p->pending[i].call;
+    while (bi < p->call_base.size() && p->call_base[bi].first < call) ++bi;
+    hipEvent_t base = (bi < p->call_base.size() && p->call_base[bi].first == call) ? p->call_base[bi].second : nullptr;
+    Window win[CARAMEL_K_COUNT] = {};
+    for (; i < p->pending.size() && p->pending[i].call == call; ++i) {
+      TimedLaunch& t = p->pending[i];
+      HIP_TRY(hipEventSynchronize(t.stop));
+      float ms = 0.f;
+      HIP_TRY(hipEventElapsedTime(&ms, t.start, t.stop));
+      p->stats[t.kind].launches += 1;
+      p->stats[t.kind].total_ms += ms;
+      if (base) {
+        float a = 0.f, b = 0.f;
+        HIP_TRY(hipEventElapsedTime(&a, base, t.start));
+        HIP_TRY(hipEventElapsedTime(&b, base, t.stop));
+        Window& w = win[t.kind];
+        if (!w.any) w = {a, b, true};
+        w.lo = std::min(w.lo, a);
+        w.hi = std::max(w.hi, b);
+      }
+      p->spare.push_back(t.start);
+      p->spare.push_back(t.stop);
+    }
+    for (int k = 0; k < CARAMEL_K_COUNT; ++k)
+      if (win[k].any) {
+        p->stats[k].span_ms += double(win[k].hi) - double(win[k].lo);
+        p->stats[k].calls += 1;
+      }
+  }
+  p->pending.clear();
+  for (auto& b : p->call_base) p->spare.push_back(b.second);
+  p->call_base.clear();
+  std::memcpy(out, p->stats, sizeof p->stats);
+  return CARAMEL_OK;
+}
+
+const char* caramel_last_error(void) { return g_err.c_str(); }
+
+int caramel_version(void) { return 100; }
+
+}  // extern "C"

@@ -1,0 +1,308 @@
+// gfx950 kernels of the aggregation path.  Everything here is bandwidth work: 128-bit
+// coalesced loads and stores, no matrix cores.
+//
+//  k_ring_reduce   ring reduce-scatter arithmetic, 1/W scaling and all-gather (paper
+//                  sections 2 and 4.4: partial sums travel round the ring and are added to
+//                  at each worker; the owner's result is then copied to every worker).
+//                  A workgroup handles one tile, which lies inside one ring segment, so the
+//                  chain of workers  first, first+1, ...  is the same for all lanes and the
+//                  W base pointers live in scalar registers.
+//  k_copy          pack / unpack of batched parameters (section 4.2) through an offset table,
+//                  one wavefront per run.
+#include "kernels.hpp"
+
+namespace caramel {
+namespace {
+
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+// Pointers built from table entries are declared as global-memory pointers so that loads and
+// stores use the global (scalar base + lane offset) form rather than the generic one.
+#define CARAMEL_GLOBAL __attribute__((address_space(1)))
+typedef CARAMEL_GLOBAL u32x4* gvec_ptr;
+typedef CARAMEL_GLOBAL float* gf32_ptr;
+typedef CARAMEL_GLOBAL uint16_t* gu16_ptr;
+typedef CARAMEL_GLOBAL uint32_t* gu32_ptr;
+
+constexpr int kBlock = 256;
+
+template <bool NT>
+__device__ __forceinline__ u32x4 ld(gvec_ptr p) {
+  if constexpr (NT) return __builtin_nontemporal_load(p);
+  else return *p;
+}
+template <bool NT>
+__device__ __forceinline__ void st(gvec_ptr p, u32x4 v) {
+  if constexpr (NT) __builtin_nontemporal_store(v, p);
+  else *p = v;
+}
+
+// scalar base + 32-bit lane byte offset
+__device__ __forceinline__ gvec_ptr at(gvec_ptr base, uint32_t byte_off) {
+  return reinterpret_cast<gvec_ptr>(reinterpret_cast<CARAMEL_GLOBAL char*>(base) + byte_off);
+}
+
+__device__ __forceinline__ f32x4 bits_to_f32(u32x4 v) { return __builtin_bit_cast(f32x4, v); }
+__device__ __forceinline__ u32x4 f32_to_bits(f32x4 v) { return __builtin_bit_cast(u32x4, v); }
+
+// fp32 -> bf16, round to nearest, ties to even; NaN stays a (quiet) NaN.
+__device__ __forceinline__ uint32_t bf16_rne(float f) {
+  const uint32_t b = __float_as_uint(f);
+  const uint32_t r = (b + 0x7FFFu + ((b >> 16) & 1u)) >> 16;
+  return (f != f) ? ((b >> 16) | 0x40u) : r;
+}
+
+// Running ring sum of one 16-byte vector.  F32: four lanes.  BF16: eight values, kept as the
+// even-indexed (low halves) and odd-indexed (high halves) quartets, widened exactly.
+template <bool BF16>
+struct Chain {
+  f32x4 a, b;
+  __device__ __forceinline__ void start(u32x4 x) {
+    if constexpr (BF16) {
+      a = bits_to_f32(x << 16);
+      b = bits_to_f32(x & 0xFFFF0000u);
+    } else {
+      a = bits_to_f32(x);
+    }
+  }
+  __device__ __forceinline__ void add(u32x4 x) {
+    if constexpr (BF16) {
+      a = a + bits_to_f32(x << 16);
+      b = b + bits_to_f32(x & 0xFFFF0000u);
+    } else {
+      a = a + bits_to_f32(x);
+    }
+  }
+  __device__ __forceinline__ u32x4 finish(float inv_w) {
+    if constexpr (BF16) {
+      const f32x4 ya = a * inv_w, yb = b * inv_w;
+      u32x4 r;
+      r.x = bf16_rne(ya.x) | (bf16_rne(yb.x) << 16);
+      r.y = bf16_rne(ya.y) | (bf16_rne(yb.y) << 16);
+      r.z = bf16_rne(ya.z) | (bf16_rne(yb.z) << 16);
+      r.w = bf16_rne(ya.w) | (bf16_rne(yb.w) << 16);
+      return r;
+    } else {
+      return f32_to_bits(a * inv_w);
+    }
+  }
+};
+
+__device__ __forceinline__ float widen(uint16_t h) { return __uint_as_float(uint32_t(h) << 16); }
+
+// ------------------------------------------------------------------------------------------
+// W known at compile time: all W loads of a vector (times U vectors) are issued before the
+// first add, so each lane keeps W*U 128-bit requests in flight.
+template <int W, int U, bool BF16, bool NT>
+__global__ void __launch_bounds__(kBlock)
+k_ring_reduce(const ReduceTile* __restrict__ tiles, const uint64_t* __restrict__ rows, uint32_t begin,
+              uint32_t count, float inv_w) {
+  constexpr uint32_t VE = BF16 ? 8 : 4;
+  for (uint32_t ti = blockIdx.x; ti < count; ti += gridDim.x) {
+    const ReduceTile tl = tiles[begin + ti];
+    gvec_ptr p[W];
+#pragma unroll
+    for (int k = 0; k < W; ++k) {
+      uint32_t w = tl.first + k;
+      if (w >= uint32_t(W)) w -= W;
+      p[k] = reinterpret_cast<gvec_ptr>(rows[size_t(tl.row) * W + w]) + tl.vec_off;
+    }
+    const uint32_t nvec = tl.n_elems / VE;
+    uint32_t v = threadIdx.x;
+    // lane offsets are 32-bit byte offsets from the scalar bases (a tile spans < 2^24 bytes)
+    for (; v + (U - 1) * kBlock < nvec; v += U * kBlock) {
+      u32x4 x[U][W];
+#pragma unroll
+      for (int u = 0; u < U; ++u)
+#pragma unroll
+        for (int k = 0; k < W; ++k) x[u][k] = ld<NT>(at(p[k], (v + u * kBlock) * 16u));
+      __builtin_amdgcn_sched_barrier(0);  // keep all loads ahead of the arithmetic
+#pragma unroll
+      for (int u = 0; u < U; ++u) {
+        Chain<BF16> c;
+        c.start(x[u][0]);
+#pragma unroll
+        for (int k = 1; k < W; ++k) c.add(x[u][k]);
+        const u32x4 y = c.finish(inv_w);
+#pragma unroll
+        for (int k = 0; k < W; ++k) st<NT>(at(p[k], (v + u * kBlock) * 16u), y);
+      }
+    }
+    for (; v < nvec; v += kBlock) {
+      u32x4 x[W];
+#pragma unroll
+      for (int k = 0; k < W; ++k) x[k] = ld<NT>(at(p[k], v * 16u));
+      __builtin_amdgcn_sched_barrier(0);
+      Chain<BF16> c;
+      c.start(x[0]);
+#pragma unroll
+      for (int k = 1; k < W; ++k) c.add(x[k]);
+      const u32x4 y = c.finish(inv_w);
+#pragma unroll
+      for (int k = 0; k < W; ++k) st<NT>(at(p[k], v * 16u), y);
+    }
+    // a run that ends a tensor may stop inside a vector: finish it element by element
+    const uint32_t rem = tl.n_elems - nvec * VE;
+    if (threadIdx.x < rem) {
+      const uint32_t e = nvec * VE + threadIdx.x;
+      if constexpr (BF16) {
+        float acc = widen(reinterpret_cast<gu16_ptr>(p[0])[e]);
+#pragma unroll
+        for (int k = 1; k < W; ++k) acc = acc + widen(reinterpret_cast<gu16_ptr>(p[k])[e]);
+        const uint16_t y = uint16_t(bf16_rne(acc * inv_w));
+#pragma unroll
+        for (int k = 0; k < W; ++k) reinterpret_cast<gu16_ptr>(p[k])[e] = y;
+      } else {
+        float acc = reinterpret_cast<gf32_ptr>(p[0])[e];
+#pragma unroll
+        for (int k = 1; k < W; ++k) acc = acc + reinterpret_cast<gf32_ptr>(p[k])[e];
+        const float y = acc * inv_w;
+#pragma unroll
+        for (int k = 0; k < W; ++k) reinterpret_cast<gf32_ptr>(p[k])[e] = y;
+      }
+    }
+  }
+}
+
+// Any W: pointers are fetched as the chain advances.
+template <bool BF16, bool NT>
+__global__ void __launch_bounds__(kBlock)
+k_ring_reduce_any(const ReduceTile* __restrict__ tiles, const uint64_t* __restrict__ rows, uint32_t begin,
+                  uint32_t count, uint32_t W, float inv_w) {
+  constexpr uint32_t VE = BF16 ? 8 : 4;
+  for (uint32_t ti = blockIdx.x; ti < count; ti += gridDim.x) {
+    const ReduceTile tl = tiles[begin + ti];
+    const uint64_t* row = rows + size_t(tl.row) * W;
+    const uint32_t nvec = tl.n_elems / VE;
+    for (uint32_t v = threadIdx.x; v < nvec; v += kBlock) {
+      uint32_t w = tl.first;
+      Chain<BF16> c;
+      c.start(ld<NT>(reinterpret_cast<gvec_ptr>(row[w]) + tl.vec_off + v));
+      for (uint32_t k = 1; k < W; ++k) {
+        w = (w + 1 == W) ? 0 : w + 1;
+        c.add(ld<NT>(reinterpret_cast<gvec_ptr>(row[w]) + tl.vec_off + v));
+      }
+      const u32x4 y = c.finish(inv_w);
+      for (uint32_t k = 0; k < W; ++k) st<NT>(reinterpret_cast<gvec_ptr>(row[k]) + tl.vec_off + v, y);
+    }
+    const uint32_t rem = tl.n_elems - nvec * VE;
+    if (threadIdx.x < rem) {
+      const size_t e = size_t(tl.vec_off) * VE + nvec * VE + threadIdx.x;
+      uint32_t w = tl.first;
+      if constexpr (BF16) {
+        float acc = widen(reinterpret_cast<gu16_ptr>(row[w])[e]);
+        for (uint32_t k = 1; k < W; ++k) {
+          w = (w + 1 == W) ? 0 : w + 1;
+          acc = acc + widen(reinterpret_cast<gu16_ptr>(row[w])[e]);
+        }
+        const uint16_t y = uint16_t(bf16_rne(acc * inv_w));
+        for (uint32_t k = 0; k < W; ++k) reinterpret_cast<gu16_ptr>(row[k])[e] = y;
+      } else {
+        float acc = reinterpret_cast<gf32_ptr>(row[w])[e];
+        for (uint32_t k = 1; k < W; ++k) {
+          w = (w + 1 == W) ? 0 : w + 1;
+          acc = acc + reinterpret_cast<gf32_ptr>(row[w])[e];
+        }
+        const float y = acc * inv_w;
+        for (uint32_t k = 0; k < W; ++k) reinterpret_cast<gf32_ptr>(row[k])[e] = y;
+      }
+    }
+  }
+}
+
+// ------------------------------------------------------------------------------------------
+// pack / unpack: one wavefront per copy tile, grid.y = worker.
+template <typename E, bool UNPACK>
+__global__ void __launch_bounds__(kBlock)
+k_copy(const CopyTile* __restrict__ tiles, const uint64_t* __restrict__ rows, uint32_t begin, uint32_t count,
+       uint32_t W, uint32_t fused_row) {
+  constexpr uint32_t VE = 16 / sizeof(E);
+  const uint32_t lane = threadIdx.x & 63u;
+  const uint32_t ti = __builtin_amdgcn_readfirstlane(blockIdx.x * (kBlock / 64) + (threadIdx.x >> 6));
+  if (ti >= count) return;
+  const CopyTile t = tiles[begin + ti];
+  const uint32_t w = blockIdx.y;
+  gvec_ptr tp = reinterpret_cast<gvec_ptr>(rows[size_t(t.row) * W + w]) + t.t_vec_off;
+  gvec_ptr fp = reinterpret_cast<gvec_ptr>(rows[size_t(fused_row) * W + w]) + t.f_vec_off;
+  const uint32_t nvec = t.n_elems / VE;
+  gvec_ptr src = UNPACK ? fp : tp;
+  gvec_ptr dst = UNPACK ? tp : fp;
+  uint32_t v = lane;
+  for (; v + 3 * 64 < nvec; v += 4 * 64) {
+    const u32x4 a = src[v], b = src[v + 64], c = src[v + 128], d = src[v + 192];
+    dst[v] = a;
+    dst[v + 64] = b;
+    dst[v + 128] = c;
+    dst[v + 192] = d;
+  }
+  for (; v < nvec; v += 64) dst[v] = src[v];
+  // ragged end of a member, and (pack only) the +0.0 padding up to the next member
+  CARAMEL_GLOBAL E* se = reinterpret_cast<CARAMEL_GLOBAL E*>(src);
+  CARAMEL_GLOBAL E* de = reinterpret_cast<CARAMEL_GLOBAL E*>(dst);
+  const uint32_t end = UNPACK ? t.n_elems : t.n_elems + t.n_zero;
+  for (uint32_t e = nvec * VE + lane; e < end; e += 64) de[e] = (e < t.n_elems) ? se[e] : E(0);
+}
+
+template <int W, int U>
+hipError_t launch_w(const ReduceArgs& a, dim3 grid, float inv_w, hipStream_t s) {
+#define CARAMEL_GO(BF, NT) \
+  hipLaunchKernelGGL((k_ring_reduce<W, U, BF, NT>), grid, dim3(kBlock), 0, s, a.tiles, a.rows, a.begin, a.count, inv_w)
+  if (a.bf16) {
+    if (a.nontemporal) CARAMEL_GO(true, true); else CARAMEL_GO(true, false);
+  } else {
+    if (a.nontemporal) CARAMEL_GO(false, true); else CARAMEL_GO(false, false);
+  }
+#undef CARAMEL_GO
+  return hipGetLastError();
+}
+
+template <int W>
+hipError_t launch_u(const ReduceArgs& a, dim3 grid, float inv_w, hipStream_t s) {
+  uint32_t u = a.unroll;
+  if (u == 0) u = W <= 4 ? 4 : (W <= 8 ? 2 : 1);
+  if (u >= 4) return launch_w<W, 4>(a, grid, inv_w, s);
+  if (u >= 2) return launch_w<W, 2>(a, grid, inv_w, s);
+  return launch_w<W, 1>(a, grid, inv_w, s);
+}
+
+}  // namespace
+
+hipError_t launch_ring_reduce(const ReduceArgs& a, hipStream_t s) {
+  if (a.count == 0) return hipSuccess;
+  uint32_t g = a.count;
+  if (a.max_grid && g > a.max_grid) g = a.max_grid;
+  const dim3 grid(g);
+  const float inv_w = 1.0f / float(a.world);
+  switch (a.world) {
+    case 2: return launch_u<2>(a, grid, inv_w, s);
+    case 4: return launch_u<4>(a, grid, inv_w, s);
+    case 8: return launch_u<8>(a, grid, inv_w, s);
+    case 16: return launch_u<16>(a, grid, inv_w, s);
+    default: break;
+  }
+#define CARAMEL_ANY(BF, NT) \
+  hipLaunchKernelGGL((k_ring_reduce_any<BF, NT>), grid, dim3(kBlock), 0, s, a.tiles, a.rows, a.begin, a.count, a.world, inv_w)
+  if (a.bf16) {
+    if (a.nontemporal) CARAMEL_ANY(true, true); else CARAMEL_ANY(true, false);
+  } else {
+    if (a.nontemporal) CARAMEL_ANY(false, true); else CARAMEL_ANY(false, false);
+  }
+#undef CARAMEL_ANY
+  return hipGetLastError();
+}
+
+hipError_t launch_copy(const CopyArgs& a, hipStream_t s) {
+  if (a.count == 0) return hipSuccess;
+  const dim3 grid((a.count + kBlock / 64 - 1) / (kBlock / 64), a.world);
+#define CARAMEL_CP(E, UN) \
+  hipLaunchKernelGGL((k_copy<E, UN>), grid, dim3(kBlock), 0, s, a.tiles, a.rows, a.begin, a.count, a.world, a.fused_row)
+  if (a.bf16) {
+    if (a.unpack) CARAMEL_CP(uint16_t, true); else CARAMEL_CP(uint16_t, false);
+  } else {
+    if (a.unpack) CARAMEL_CP(uint32_t, true); else CARAMEL_CP(uint32_t, false);
+  }
+#undef CARAMEL_CP
+  return hipGetLastError();
+}
+
+}  // namespace caramel

@@ -1,0 +1,36 @@
+// Launch wrappers for the gfx950 kernels.
+#pragma once
+
+#include <hip/hip_runtime.h>
+
+#include "tiles.hpp"
+
+namespace caramel {
+
+struct ReduceArgs {
+  const ReduceTile* tiles;  // device
+  const uint64_t* rows;     // device: (n_rows x W) base pointers
+  uint32_t begin, count;    // tile range
+  uint32_t world;
+  bool bf16;
+  bool nontemporal;
+  uint32_t unroll;    // vectors in flight per lane and worker: 1, 2 or 4 (0 = choose from W)
+  uint32_t max_grid;  // 0 = one workgroup per tile
+};
+
+struct CopyArgs {
+  const CopyTile* tiles;  // device
+  const uint64_t* rows;   // device
+  uint32_t begin, count;
+  uint32_t world;
+  uint32_t fused_row;
+  bool bf16;
+  bool unpack;  // false: tensors -> fused buffers; true: fused buffers -> tensors
+};
+
+// Ring reduce-scatter arithmetic + 1/W scaling + all-gather for a range of tiles.
+hipError_t launch_ring_reduce(const ReduceArgs& a, hipStream_t stream);
+// Segmented gather (pack) or scatter (unpack) driven by the copy-tile table.
+hipError_t launch_copy(const CopyArgs& a, hipStream_t stream);
+
+}  // namespace caramel

@@ -1,0 +1,49 @@
+// Descriptor tables that drive the kernels.  Built on the host from a HostPlan, uploaded at
+// bind time.  All offsets are in 16-byte vectors relative to a "pointer row": row t < n_tensors
+// is tensor t (one base pointer per worker), row n_tensors is the fused workspace.
+#pragma once
+
+#include <cstdint>
+#include <vector>
+
+#include "plan.hpp"
+
+namespace caramel {
+
+// One workgroup's share of the ring reduction: a run of elements that lies inside ONE ring
+// segment, so the chain of workers is the same for every lane.
+struct ReduceTile {
+  uint32_t row;      // pointer row
+  uint32_t first;    // worker whose value starts the chain: (segment + 1) mod W
+  uint32_t vec_off;  // offset of the run inside the row, in 16-byte vectors
+  uint32_t n_elems;  // elements in the run; only a run that ends a tensor may be ragged
+};
+
+// One wavefront's share of pack / unpack: a run of one batch member.
+struct CopyTile {
+  uint32_t row;        // tensor row
+  uint32_t t_vec_off;  // offset inside the tensor, in vectors
+  uint32_t f_vec_off;  // offset inside a replica's fused buffer, in vectors
+  uint32_t n_elems;    // elements to copy
+  uint32_t n_zero;     // padding elements that follow in the fused buffer (pack writes +0.0)
+  uint32_t pad_[3];
+};
+
+struct Range {
+  uint32_t begin = 0, count = 0;
+};
+
+struct TileTables {
+  std::vector<ReduceTile> staged;  // batch units on the fused row, chunk units on tensor rows
+  std::vector<ReduceTile> direct;  // batch units addressed through their member tensors
+  std::vector<CopyTile> copy;
+  // tile ranges per unit and per internal stream (tables are ordered by stream, then unit)
+  std::vector<Range> staged_unit, direct_unit, copy_unit;
+  Range staged_stream[2], direct_stream[2], copy_stream[2];
+  std::vector<uint32_t> stream_units[2];  // unit indices in launch order
+};
+
+// tile_vecs: vectors per reduce tile; copy_vecs: vectors per copy tile.
+void build_tiles(const HostPlan& p, uint32_t tile_vecs, uint32_t copy_vecs, TileTables& out);
+
+}  // namespace caramel

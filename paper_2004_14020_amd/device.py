@@ -1,0 +1,97 @@
+"""Device memory plumbing (PyTorch): replica arenas, uploads, downloads.
+
+No arithmetic of the method happens here; tensors are only containers whose
+addresses are handed to the library.
+"""
+from __future__ import annotations
+
+from typing import List, Optional, Sequence
+
+import numpy as np
+import torch
+
+from .binding import BF16, F32, Plan
+
+
+def _round_up(x: int, a: int) -> int:
+    return (x + a - 1) // a * a
+
+
+class Replicas:
+    """W replicas of a gradient set in device memory, one contiguous arena per replica.
+
+    Tensor t of every replica starts `slot` bytes into its arena, slots being rounded up
+    to `slot_align` bytes, like the flat gradient buffer of a training framework."""
+
+    def __init__(self, plan: Plan, elems: Sequence[int], device: str = "cuda:0", slot_align: int = 256,
+                 with_workspace: bool = True):
+        self.plan = plan
+        self.world = plan.cfg.world
+        self.elems = [int(e) for e in elems]
+        self.es = 4 if plan.cfg.dtype == F32 else 2
+        self.np_dtype = np.float32 if plan.cfg.dtype == F32 else np.uint16
+        self.torch_dtype = torch.float32 if plan.cfg.dtype == F32 else torch.int16
+        self.device = torch.device(device)
+        offs, at = [], 0
+        for n in self.elems:
+            offs.append(at)
+            at = _round_up(at + n * self.es, slot_align)
+        self.offsets = offs
+        self.arena_bytes = max(at, slot_align)
+        self.arenas = [torch.empty(self.arena_bytes, dtype=torch.uint8, device=self.device)
+                       for _ in range(self.world)]
+        fe = plan.fused_elems
+        self.fused: Optional[torch.Tensor] = None
+        if with_workspace and fe > 0:
+            self.fused = torch.empty(self.world * fe * self.es, dtype=torch.uint8, device=self.device)
+        ptrs = [[a.data_ptr() + o for o in offs] for a in self.arenas]
+        plan.bind(ptrs, self.fused.data_ptr() if self.fused is not None else None)
+
+    def rebind(self) -> None:
+        ptrs = [[a.data_ptr() + o for o in self.offsets] for a in self.arenas]
+        self.plan.bind(ptrs, self.fused.data_ptr() if self.fused is not None else None)
+
+    def tensor(self, w: int, t: int) -> torch.Tensor:
+        o, n = self.offsets[t], self.elems[t]
+        return self.arenas[w][o:o + n * self.es].view(self.torch_dtype)
+
+    def upload(self, grads: List[List[np.ndarray]]) -> None:
+        for w in range(self.world):
+            host = np.zeros(self.arena_bytes, dtype=np.uint8)
+            for t, o in enumerate(self.offsets):
+                src = np.ascontiguousarray(grads[w][t]).view(np.uint8)
+                host[o:o + src.size] = src
+            self.arenas[w].copy_(torch.from_numpy(host))
+        torch.cuda.synchronize(self.device)
+
+    def download(self) -> List[List[np.ndarray]]:
+        torch.cuda.synchronize(self.device)
+        out = []
+        for w in range(self.world):
+            host = self.arenas[w].cpu().numpy()
+            out.append([host[o:o + n * self.es].view(self.np_dtype).copy()
+                        for o, n in zip(self.offsets, self.elems)])
+        return out
+
+    def download_fused(self) -> Optional[np.ndarray]:
+        if self.fused is None:
+            return None
+        torch.cuda.synchronize(self.device)
+        return self.fused.cpu().numpy().view(self.np_dtype).reshape(self.world, -1).copy()
+
+    def fill_fused(self, byte: int) -> None:
+        if self.fused is not None:
+            self.fused.fill_(byte)
+
+    def fill_random(self, seed: int = 0) -> None:
+        """Device-side fill for timing runs only (values do not affect speed)."""
+        g = torch.Generator(device=self.device)
+        g.manual_seed(seed)
+        for w in range(self.world):
+            n = self.arena_bytes // 4
+            v = self.arenas[w][:n * 4].view(torch.float32)
+            v.normal_(0.0, 1e-2, generator=g)
+            if self.es == 2:
+                # keep bf16 halves finite: clear the low exponent/mantissa mix of odd halves
+                self.arenas[w][:n * 4].view(torch.int16).bitwise_and_(0x3FFF)
+        torch.cuda.synchronize(self.device)

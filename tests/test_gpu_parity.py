@@ -1,0 +1,222 @@
+"""GPU parity: the HIP path against the CPU oracle, bit for bit, through the C ABI.
+
+Integer/byte work (plan, pack, unpack) and the fixed-order fp32 ring sums both have exactly
+one correct bit pattern per element, so every comparison is on raw bits.  The float64 bound
+|y - mean| <= 4e-7 * sum_w |g_w| is checked as well.
+"""
+import numpy as np
+import pytest
+
+import oracle
+import paper_2004_14020_amd as cm
+from paper_2004_14020_amd.device import Replicas
+from workloads.shapes import ALL, workload
+
+from gpu_util import assert_same_bits, bits, clone, lib_plan, make_inputs, oracle_result
+
+pytestmark = pytest.mark.gpu
+
+# spans several reduce tiles (1024 vectors = 4096 fp32 each), ragged tails, members that are
+# smaller than one granule, and units with fewer granules than workers (empty ring segments)
+SMALL_ELEMS = (10, 700, 33, 50000, 1, 257, 30011, 64, 129, 3, 4097, 100000, 7, 20000)
+
+
+def small_cfg(W, dtype, streams=2, T=8192, mode=oracle.SPLIT_FIXED, S=65536, align=16):
+    return oracle.Config(W, dtype, T, mode, 8, S, align, streams)
+
+
+@pytest.mark.parametrize("W", [1, 2, 3, 4, 5, 8, 16, 33])
+@pytest.mark.parametrize("dtype", [oracle.F32, oracle.BF16])
+def test_each_stage_matches_the_oracle(W, dtype):
+    print(f"case: stages W={W} dtype={dtype}", flush=True)
+    cfg = small_cfg(W, dtype)
+    elems = list(SMALL_ELEMS)
+    grads = make_inputs(cfg, elems, seed=W)
+    oplan = oracle.build_plan(cfg, elems)
+    ref = clone(grads)
+    ofused = oracle.new_fused(oplan)
+
+    plan = lib_plan(cfg, elems)
+    dev = Replicas(plan, elems)
+    dev.upload(grads)
+    dev.fill_fused(0xA5)
+
+    plan.pack()
+    oracle.pack(oplan, ref, ofused)
+    assert np.array_equal(bits(dev.download_fused()), bits(ofused)), "fused buffer after pack"
+    assert_same_bits(dev.download(), ref, "tensors after pack")
+
+    plan.ring_reduce()
+    oracle.ring_reduce(oplan, ref, ofused)
+    assert np.array_equal(bits(dev.download_fused()), bits(ofused)), "fused buffer after ring_reduce"
+    assert_same_bits(dev.download(), ref, "tensors after ring_reduce")
+
+    plan.unpack()
+    oracle.unpack(oplan, ref, ofused)
+    assert_same_bits(dev.download(), ref, "tensors after unpack")
+    plan.close()
+
+
+MODES = [(cm.LAUNCH_PER_UNIT, cm.BATCH_STAGED), (cm.LAUNCH_PER_UNIT, cm.BATCH_DIRECT),
+         (cm.LAUNCH_PER_STREAM, cm.BATCH_STAGED), (cm.LAUNCH_PER_STREAM, cm.BATCH_DIRECT)]
+
+
+@pytest.mark.parametrize("W,dtype", [(4, oracle.F32), (8, oracle.F32), (8, oracle.BF16), (16, oracle.F32),
+                                     (5, oracle.F32), (3, oracle.BF16)])
+@pytest.mark.parametrize("launch,batch", MODES)
+@pytest.mark.parametrize("streams", [1, 2])
+def test_allreduce_all_modes(W, dtype, launch, batch, streams):
+    print(f"case: allreduce W={W} dtype={dtype} launch={launch} batch={batch} streams={streams}", flush=True)
+    cfg = small_cfg(W, dtype, streams)
+    elems = list(SMALL_ELEMS)
+    grads = make_inputs(cfg, elems, seed=100 + W)
+    ref = oracle_result(cfg, elems, grads)
+    plan = lib_plan(cfg, elems, **{cm.OPT_LAUNCH_MODE: launch, cm.OPT_BATCH_PATH: batch})
+    dev = Replicas(plan, elems)
+    dev.upload(grads)
+    plan.allreduce()
+    assert_same_bits(dev.download(), ref, "allreduce")
+    plan.close()
+
+
+@pytest.mark.parametrize("opts", [
+    {cm.OPT_TILE_VECS: 64}, {cm.OPT_TILE_VECS: 256, cm.OPT_UNROLL: 4}, {cm.OPT_TILE_VECS: 4096, cm.OPT_UNROLL: 1},
+    {cm.OPT_MAX_GRID: 7}, {cm.OPT_NONTEMPORAL: 0}, {cm.OPT_UNROLL: 2, cm.OPT_MAX_GRID: 300},
+])
+@pytest.mark.parametrize("dtype", [oracle.F32, oracle.BF16])
+def test_launch_options_do_not_change_results(opts, dtype):
+    print(f"case: options {opts} dtype={dtype}", flush=True)
+    cfg = small_cfg(8, dtype)
+    elems = list(SMALL_ELEMS)
+    grads = make_inputs(cfg, elems, seed=7)
+    ref = oracle_result(cfg, elems, grads)
+    plan = lib_plan(cfg, elems, **opts)
+    dev = Replicas(plan, elems)
+    dev.upload(grads)
+    plan.allreduce()
+    assert_same_bits(dev.download(), ref, f"options {opts}")
+    plan.close()
+
+
+@pytest.mark.parametrize("align", [16, 64, 256])
+@pytest.mark.parametrize("mode,S", [(oracle.SPLIT_NONE, 0), (oracle.SPLIT_ADAPTIVE, 16384)])
+def test_alignment_and_split_modes(align, mode, S):
+    print(f"case: align={align} mode={mode}", flush=True)
+    cfg = small_cfg(8, oracle.F32, 2, 16384, mode, S, align)
+    elems = list(SMALL_ELEMS)
+    grads = make_inputs(cfg, elems, seed=align)
+    ref = oracle_result(cfg, elems, grads)
+    for batch in (cm.BATCH_STAGED, cm.BATCH_DIRECT):
+        plan = lib_plan(cfg, elems, **{cm.OPT_BATCH_PATH: batch})
+        dev = Replicas(plan, elems)
+        dev.upload(grads)
+        plan.allreduce()
+        assert_same_bits(dev.download(), ref, f"align {align} batch path {batch}")
+        plan.close()
+
+
+def test_batching_off_and_single_tiny_tensor():
+    for elems, T in (([1], 0), ([3, 5], 0), ([2], 1 << 20), ([5, 3, 9], 1 << 20)):
+        for W in (1, 4, 16):
+            print(f"case: tiny elems={elems} T={T} W={W}", flush=True)
+            cfg = oracle.Config(W, oracle.F32, T, oracle.SPLIT_NONE, 8, 0, 16, 2)
+            grads = make_inputs(cfg, elems, seed=1)
+            ref = oracle_result(cfg, elems, grads)
+            plan = lib_plan(cfg, elems)
+            dev = Replicas(plan, elems)
+            dev.upload(grads)
+            plan.allreduce()
+            assert_same_bits(dev.download(), ref, "tiny")
+            plan.close()
+
+
+def test_special_values_follow_ieee():
+    """Denormals are kept (no flush to zero), infinities propagate, and the hand-worked
+    rotation example gives the four distinct per-segment results."""
+    W, n = 4, 52
+    cfg = oracle.Config(W, oracle.F32, 0)
+    tiny = np.float32(1e-45)
+    rows = [np.full(n, v, dtype=np.float32) for v in (tiny, tiny * 3, -tiny, tiny * 5)]
+    rows[0][5] = np.inf
+    rows[1][6] = -np.inf
+    rows[2][7] = np.float32(3.0e38)
+    rows[3][7] = np.float32(3.0e38)
+    grads = [[r] for r in rows]
+    ref = oracle_result(cfg, [n], grads)
+    plan = lib_plan(cfg, [n])
+    dev = Replicas(plan, [n])
+    dev.upload(grads)
+    plan.allreduce()
+    got = dev.download()
+    assert_same_bits(got, ref, "special values")
+    assert got[0][0][0] == tiny * 2 and np.isinf(got[0][0][5]) and np.isinf(got[0][0][7])
+    plan.close()
+
+    ex = [1.0, 33554432.0, -33554432.0, 5.0]
+    grads = [[np.full(n, g, dtype=np.float32)] for g in ex]
+    plan = lib_plan(cfg, [n])
+    dev = Replicas(plan, [n])
+    dev.upload(grads)
+    plan.allreduce()
+    got = dev.download()
+    seg = plan.segments(0)
+    for c, want in enumerate([1.5, 1.0, 2.0, 1.25]):
+        for w in range(W):
+            assert (got[w][0][seg[c]:seg[c + 1]] == np.float32(want)).all()
+    plan.close()
+
+
+def test_repeated_calls_are_race_free_and_idempotent_on_the_result():
+    """20 back-to-back allreduce calls on one and on two streams: after the first call all
+    replicas are equal, so for W = 4 every further call must leave the bits unchanged
+    (x + x, 3x -> 4x is recovered exactly); any stream-ordering mistake would show."""
+    import torch
+    for streams in (1, 2):
+        print(f"case: repeat streams={streams}", flush=True)
+        cfg = small_cfg(4, oracle.F32, streams)
+        elems = list(SMALL_ELEMS)
+        grads = make_inputs(cfg, elems, seed=5)
+        ref = oracle_result(cfg, elems, grads)
+        plan = lib_plan(cfg, elems, **{cm.OPT_BATCH_PATH: cm.BATCH_STAGED, cm.OPT_LAUNCH_MODE: cm.LAUNCH_PER_UNIT})
+        dev = Replicas(plan, elems)
+        dev.upload(grads)
+        s = torch.cuda.Stream()
+        with torch.cuda.stream(s):
+            for _ in range(20):
+                plan.allreduce(s.cuda_stream)
+        s.synchronize()
+        assert_same_bits(dev.download(), ref, "repeat")
+        plan.close()
+
+
+def test_accuracy_bound_against_float64():
+    cfg = small_cfg(16, oracle.F32)
+    elems = list(SMALL_ELEMS)
+    grads = make_inputs(cfg, elems, seed=3)
+    oplan = oracle.build_plan(cfg, elems)
+    mean = [oracle.mean_f64(oplan, grads, t) for t in range(len(elems))]
+    mag = [oracle.abs_sum_f64(oplan, grads, t) for t in range(len(elems))]
+    plan = lib_plan(cfg, elems)
+    dev = Replicas(plan, elems)
+    dev.upload(grads)
+    plan.allreduce()
+    got = dev.download()
+    for t in range(len(elems)):
+        assert (np.abs(got[0][t].astype(np.float64) - mean[t]) <= 4e-7 * mag[t]).all()
+    plan.close()
+
+
+def test_profile_counters():
+    cfg = small_cfg(8, oracle.F32)
+    elems = list(SMALL_ELEMS)
+    plan = lib_plan(cfg, elems, **{cm.OPT_BATCH_PATH: cm.BATCH_STAGED})
+    dev = Replicas(plan, elems)
+    dev.upload(make_inputs(cfg, elems, seed=3))
+    plan.profile(True)
+    for _ in range(3):
+        plan.allreduce()
+    st = plan.profile_read()
+    assert st[cm.K_REDUCE]["launches"] == 6 and st[cm.K_PACK]["launches"] == 6 and st[cm.K_UNPACK]["launches"] == 6
+    assert st[cm.K_REDUCE]["calls"] == 3 and 0 < st[cm.K_REDUCE]["span_ms"] <= st[cm.K_REDUCE]["total_ms"] * 1.01 + 1e-3
+    plan.profile(False)
+    plan.close()

@@ -1,0 +1,132 @@
+"""Host logic of the library, checked on the CPU: exported symbols, the planner against the
+oracle's plan (bit-exact, integers), argument errors.  No GPU call is made."""
+import ctypes
+import os
+import random
+import re
+import struct
+
+import pytest
+
+import oracle
+import paper_2004_14020_amd as cm
+from paper_2004_14020_amd import binding
+from workloads.shapes import ALL, workload
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def lib_plan(cfg: oracle.Config, elems):
+    return cm.Plan(cfg.world, elems, dtype=cfg.dtype, batch_threshold_bytes=cfg.batch_threshold_bytes,
+                   split_mode=cfg.split_mode, split_bytes=cfg.split_bytes, max_depth=cfg.max_depth,
+                   align_bytes=cfg.align_bytes, num_streams=cfg.num_streams)
+
+
+def assert_same_plan(cfg, elems):
+    ref = oracle.build_plan(cfg, elems)
+    got = lib_plan(cfg, elems)
+    nu, ne, fe = got.counts()
+    assert (nu, ne, fe) == (len(ref.units), len(ref.entries), ref.fused_elems)
+    for i, (u, r) in enumerate(zip(got.units(), ref.units)):
+        assert (u.kind, u.stream, u.first_entry, u.n_entries, u.elems, u.fused_off) == \
+               (r.kind, r.stream, r.first_entry, r.n_entries, r.elems, r.fused_off)
+        assert got.segments(i) == r.seg_start
+    for e, r in zip(got.entries(), ref.entries):
+        assert (e.tensor, e.unit, e.tensor_off, e.unit_off, e.elems) == \
+               (r.tensor, r.unit, r.tensor_off, r.unit_off, r.elems)
+    got.close()
+
+
+def test_every_declared_symbol_is_exported():
+    with open(os.path.join(ROOT, "include", "caramel.h")) as f:
+        header = f.read()
+    declared = set(re.findall(r"\b(caramel_[a-z_]+)\s*\(", header))
+    assert declared == set(binding.EXPORTS)
+    L = ctypes.CDLL(binding.LIB_PATH)
+    for name in declared:
+        assert getattr(L, name) is not None
+    assert cm.caramel_version() >= 100
+
+
+@pytest.mark.parametrize("name", ALL)
+def test_plan_equals_oracle_on_workloads(name):
+    wl = workload(name)
+    cfg = oracle.Config(wl.world, wl.dtype, wl.batch_threshold_bytes, wl.split_mode, wl.max_depth,
+                        wl.split_bytes, wl.align_bytes, wl.num_streams)
+    assert_same_plan(cfg, wl.elems())
+
+
+def test_plan_equals_oracle_on_random_inputs():
+    rng = random.Random(414020)
+    for _ in range(400):
+        dtype = rng.choice([oracle.F32, oracle.BF16])
+        align = rng.choice([16, 16, 32, 64, 256])
+        mode = rng.choice([oracle.SPLIT_NONE, oracle.SPLIT_FIXED, oracle.SPLIT_ADAPTIVE])
+        S = rng.choice([1, 2, 4, 16, 64]) * max(align, 64) if mode else 0
+        cfg = oracle.Config(rng.choice([1, 2, 3, 4, 5, 7, 8, 16, 33, 64]), dtype,
+                            rng.choice([0, 64, 256, 1024, 4096, 1000]), mode, rng.choice([1, 2, 8]), S,
+                            align, rng.choice([1, 2]))
+        elems = [rng.choice([1, 2, 3, 5, 8, 17, 64, 100, 255, 256, 257, 1000, 4096, 5000, 70000])
+                 for _ in range(rng.randint(1, 14))]
+        assert_same_plan(cfg, elems)
+
+
+def test_serialized_image_is_canonical():
+    wl = workload("mlp")
+    a = cm.Plan(4, wl.elems(), batch_threshold_bytes=65536)
+    b = cm.Plan(4, wl.elems(), batch_threshold_bytes=65536)
+    img = a.serialize()
+    assert img == b.serialize() and img[:8] == b"CARAMEL1"
+    world, dtype, thr = struct.unpack_from("<IIQ", img, 8)
+    assert (world, dtype, thr) == (4, 0, 65536)
+    c = cm.Plan(4, wl.elems(), batch_threshold_bytes=65537)
+    assert c.serialize() != img
+
+
+@pytest.mark.parametrize("kw", [
+    dict(world=0), dict(world=65), dict(dtype=5), dict(align_bytes=8), dict(align_bytes=48),
+    dict(num_streams=0), dict(num_streams=3), dict(split_mode=3),
+    dict(split_mode=cm.SPLIT_FIXED, split_bytes=0), dict(split_mode=cm.SPLIT_FIXED, split_bytes=24),
+    dict(split_mode=cm.SPLIT_ADAPTIVE, split_bytes=1024, max_depth=0),
+])
+def test_bad_config_is_einval(kw):
+    args = dict(world=4, dtype=cm.F32, batch_threshold_bytes=1024)
+    args.update(kw)
+    world = args.pop("world")
+    with pytest.raises(cm.CaramelError) as ei:
+        cm.Plan(world, [10, 20], **args)
+    assert ei.value.status == binding.EINVAL and str(ei.value)
+
+
+def test_bad_tensor_list_is_einval():
+    for elems in ([], [4, 0, 4]):
+        with pytest.raises(cm.CaramelError) as ei:
+            cm.Plan(4, elems)
+        assert ei.value.status == binding.EINVAL
+
+
+def test_calls_on_an_unbound_plan_fail_without_touching_the_device():
+    p = cm.Plan(4, [10, 5000], batch_threshold_bytes=1024)
+    for call in (p.pack, p.ring_reduce, p.unpack, p.allreduce):
+        with pytest.raises(cm.CaramelError) as ei:
+            call()
+        assert ei.value.status == binding.ESTATE
+    with pytest.raises(cm.CaramelError) as ei:
+        p.set_option(99, 1)
+    assert ei.value.status == binding.EINVAL
+    with pytest.raises(cm.CaramelError):
+        p.set_option(cm.OPT_TILE_VECS, 3)
+
+
+def test_bind_rejects_bad_pointers_before_any_device_call():
+    p = cm.Plan(2, [10, 5000], batch_threshold_bytes=1024)
+    good = [[0x10000, 0x20000], [0x30000, 0x40000]]
+    for bad in ([[0, 0x20000], [0x30000, 0x40000]],             # NULL
+                [[0x10004, 0x20000], [0x30000, 0x40000]],       # misaligned
+                [[0x10000, 0x20000], [0x10010, 0x40000]]):      # overlapping replicas
+        with pytest.raises(cm.CaramelError) as ei:
+            p.bind(bad, 0x90000)
+        assert ei.value.status == binding.EINVAL
+    with pytest.raises(cm.CaramelError) as ei:
+        p.bind(good, 0x10020)                                    # workspace overlaps a tensor
+    assert ei.value.status == binding.EINVAL
