@@ -190,7 +190,8 @@ enum { CARAMEL_K_PACK = 0, CARAMEL_K_REDUCE = 1, CARAMEL_K_UNPACK = 2, CARAMEL_K
 /* Per-kernel timing, measured with HIP events recorded on the stream each kernel is launched
  * on.  `launches`/`total_ms` accumulate over calls since profiling was switched on; `span_ms`
  * accumulates, per call, the time from the earliest start to the latest end of that kernel's
- * launches (launches on the two internal streams overlap, so span <= total). */
+ * launches (launches on the two internal streams may overlap, and there may be gaps between
+ * launches, so span and total differ in either direction). */
 typedef struct caramel_kernel_stat {
   uint64_t launches;
   double total_ms;

@@ -68,6 +68,10 @@ def lib() -> C.CDLL:
         return _lib
     if not os.path.exists(LIB_PATH):
         raise ImportError(f"{LIB_PATH} is missing: build it with `python -m paper_2004_14020_amd.build`")
+    # PyTorch ships its own HIP runtime, and a process can only initialise one.  Importing torch
+    # first makes the library's dependency on libamdhip64 resolve to the copy torch has loaded,
+    # so device pointers and streams made by torch are valid inside the library.
+    import torch  # noqa: F401
     L = C.CDLL(LIB_PATH)
     P = C.c_void_p
     L.caramel_plan_create.argtypes = [C.POINTER(Config), C.POINTER(C.c_uint64), C.c_uint32, C.POINTER(P)]

@@ -59,7 +59,7 @@ def test_staged_path_on_a_full_workload():
     elems = wl.elems()
     print("case: inception_v3 staged/per-unit", flush=True)
     grads = make_inputs(cfg, elems, 2)
-    plan = lib_plan(cfg, elems, **{cm.OPT_BATCH_PATH: cm.BATCH_STAGED, cm.OPT_LAUNCH_MODE: cm.LAUNCH_PER_UNIT})
+    plan = lib_plan(cfg, elems, {cm.OPT_BATCH_PATH: cm.BATCH_STAGED, cm.OPT_LAUNCH_MODE: cm.LAUNCH_PER_UNIT})
     dev = Replicas(plan, elems)
     dev.upload(grads)
     plan.allreduce()
