@@ -176,12 +176,15 @@ enum {
   /* Non-zero: streaming (non-temporal) loads/stores in the reduce kernel. */
   CARAMEL_OPT_NONTEMPORAL = 4,
   /* 16-byte vectors each lane keeps in flight per worker: 1, 2 or 4; 0 = chosen from W. */
-  CARAMEL_OPT_UNROLL = 5
+  CARAMEL_OPT_UNROLL = 5,
+  /* Lanes per workgroup of the reduce kernel: 256, 512 or 1024. */
+  CARAMEL_OPT_BLOCK = 6
 };
 enum { CARAMEL_LAUNCH_PER_UNIT = 0, CARAMEL_LAUNCH_PER_STREAM = 1 };
 enum { CARAMEL_BATCH_STAGED = 0, CARAMEL_BATCH_DIRECT = 1 };
 
-/* Set a launch option; takes effect at the next caramel_bind (tables are rebuilt there).
+/* Set a launch option.  Tile sizes take effect at the next caramel_bind (tables are rebuilt
+ * there); the others at the next launch.
  * EINVAL for an unknown option or a value out of range. */
 int caramel_plan_set_option(caramel_plan* plan, uint32_t option, uint64_t value);
 

@@ -44,6 +44,7 @@ struct Options {
   uint32_t max_grid = 0;
   uint32_t nontemporal = 1;
   uint32_t unroll = 0;
+  uint32_t block = 512;
 };
 
 struct TimedLaunch {
@@ -156,6 +157,7 @@ int run_reduce(caramel_plan* p, bool direct, Range r, hipStream_t s) {
   a.nontemporal = p->opt.nontemporal != 0;
   a.unroll = p->opt.unroll;
   a.max_grid = p->opt.max_grid;
+  a.block = p->opt.block;
   Timed timer(p, CARAMEL_K_REDUCE, s);
   HIP_TRY(launch_ring_reduce(a, s));
   return CARAMEL_OK;
@@ -360,6 +362,10 @@ int caramel_plan_set_option(caramel_plan* p, uint32_t option, uint64_t value) {
     case CARAMEL_OPT_UNROLL:
       if (value != 0 && value != 1 && value != 2 && value != 4) return fail(CARAMEL_EINVAL, "unroll must be 0, 1, 2 or 4");
       p->opt.unroll = uint32_t(value);
+      return CARAMEL_OK;
+    case CARAMEL_OPT_BLOCK:
+      if (value != 256 && value != 512 && value != 1024) return fail(CARAMEL_EINVAL, "block must be 256, 512 or 1024");
+      p->opt.block = uint32_t(value);
       return CARAMEL_OK;
     default:
       return fail(CARAMEL_EINVAL, "unknown option %u", option);

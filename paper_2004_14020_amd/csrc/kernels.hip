@@ -24,7 +24,8 @@ typedef CARAMEL_GLOBAL float* gf32_ptr;
 typedef CARAMEL_GLOBAL uint16_t* gu16_ptr;
 typedef CARAMEL_GLOBAL uint32_t* gu32_ptr;
 
-constexpr int kBlock = 256;
+constexpr int kBlock = 256;      // pack / unpack workgroup
+constexpr int kMaxBlock = 1024;  // ring-reduce workgroups are 256, 512 or 1024 lanes
 
 template <bool NT>
 __device__ __forceinline__ u32x4 ld(gvec_ptr p) {
@@ -94,7 +95,7 @@ __device__ __forceinline__ float widen(uint16_t h) { return __uint_as_float(uint
 // W known at compile time: all W loads of a vector (times U vectors) are issued before the
 // first add, so each lane keeps W*U 128-bit requests in flight.
 template <int W, int U, bool BF16, bool NT>
-__global__ void __launch_bounds__(kBlock)
+__global__ void __launch_bounds__(kMaxBlock)
 k_ring_reduce(const ReduceTile* __restrict__ tiles, const uint64_t* __restrict__ rows, uint32_t begin,
               uint32_t count, float inv_w) {
   constexpr uint32_t VE = BF16 ? 8 : 4;
@@ -108,14 +109,15 @@ k_ring_reduce(const ReduceTile* __restrict__ tiles, const uint64_t* __restrict__
       p[k] = reinterpret_cast<gvec_ptr>(rows[size_t(tl.row) * W + w]) + tl.vec_off;
     }
     const uint32_t nvec = tl.n_elems / VE;
+    const uint32_t B = blockDim.x;
     uint32_t v = threadIdx.x;
     // lane offsets are 32-bit byte offsets from the scalar bases (a tile spans < 2^24 bytes)
-    for (; v + (U - 1) * kBlock < nvec; v += U * kBlock) {
+    for (; v + (U - 1) * B < nvec; v += U * B) {
       u32x4 x[U][W];
 #pragma unroll
       for (int u = 0; u < U; ++u)
 #pragma unroll
-        for (int k = 0; k < W; ++k) x[u][k] = ld<NT>(at(p[k], (v + u * kBlock) * 16u));
+        for (int k = 0; k < W; ++k) x[u][k] = ld<NT>(at(p[k], (v + u * B) * 16u));
       __builtin_amdgcn_sched_barrier(0);  // keep all loads ahead of the arithmetic
 #pragma unroll
       for (int u = 0; u < U; ++u) {
@@ -125,10 +127,10 @@ k_ring_reduce(const ReduceTile* __restrict__ tiles, const uint64_t* __restrict__
         for (int k = 1; k < W; ++k) c.add(x[u][k]);
         const u32x4 y = c.finish(inv_w);
 #pragma unroll
-        for (int k = 0; k < W; ++k) st<NT>(at(p[k], (v + u * kBlock) * 16u), y);
+        for (int k = 0; k < W; ++k) st<NT>(at(p[k], (v + u * B) * 16u), y);
       }
     }
-    for (; v < nvec; v += kBlock) {
+    for (; v < nvec; v += B) {
       u32x4 x[W];
 #pragma unroll
       for (int k = 0; k < W; ++k) x[k] = ld<NT>(at(p[k], v * 16u));
@@ -166,7 +168,7 @@ k_ring_reduce(const ReduceTile* __restrict__ tiles, const uint64_t* __restrict__
 
 // Any W: pointers are fetched as the chain advances.
 template <bool BF16, bool NT>
-__global__ void __launch_bounds__(kBlock)
+__global__ void __launch_bounds__(kMaxBlock)
 k_ring_reduce_any(const ReduceTile* __restrict__ tiles, const uint64_t* __restrict__ rows, uint32_t begin,
                   uint32_t count, uint32_t W, float inv_w) {
   constexpr uint32_t VE = BF16 ? 8 : 4;
@@ -174,7 +176,7 @@ k_ring_reduce_any(const ReduceTile* __restrict__ tiles, const uint64_t* __restri
     const ReduceTile tl = tiles[begin + ti];
     const uint64_t* row = rows + size_t(tl.row) * W;
     const uint32_t nvec = tl.n_elems / VE;
-    for (uint32_t v = threadIdx.x; v < nvec; v += kBlock) {
+    for (uint32_t v = threadIdx.x; v < nvec; v += blockDim.x) {
       uint32_t w = tl.first;
       Chain<BF16> c;
       c.start(ld<NT>(reinterpret_cast<gvec_ptr>(row[w]) + tl.vec_off + v));
@@ -246,7 +248,7 @@ k_copy(const CopyTile* __restrict__ tiles, const uint64_t* __restrict__ rows, ui
 template <int W, int U>
 hipError_t launch_w(const ReduceArgs& a, dim3 grid, float inv_w, hipStream_t s) {
 #define CARAMEL_GO(BF, NT) \
-  hipLaunchKernelGGL((k_ring_reduce<W, U, BF, NT>), grid, dim3(kBlock), 0, s, a.tiles, a.rows, a.begin, a.count, inv_w)
+  hipLaunchKernelGGL((k_ring_reduce<W, U, BF, NT>), grid, dim3(a.block), 0, s, a.tiles, a.rows, a.begin, a.count, inv_w)
   if (a.bf16) {
     if (a.nontemporal) CARAMEL_GO(true, true); else CARAMEL_GO(true, false);
   } else {
@@ -258,10 +260,12 @@ hipError_t launch_w(const ReduceArgs& a, dim3 grid, float inv_w, hipStream_t s) 
 
 template <int W>
 hipError_t launch_u(const ReduceArgs& a, dim3 grid, float inv_w, hipStream_t s) {
-  uint32_t u = a.unroll;
-  if (u == 0) u = W <= 4 ? 4 : (W <= 8 ? 2 : 1);
-  if (u >= 4) return launch_w<W, 4>(a, grid, inv_w, s);
-  if (u >= 2) return launch_w<W, 2>(a, grid, inv_w, s);
+  // W * U vectors per lane must fit the register budget of a 1024-lane workgroup
+  constexpr uint32_t kMaxU = W <= 4 ? 4 : (W <= 8 ? 2 : 1);
+  uint32_t u = a.unroll ? a.unroll : kMaxU;
+  if (u > kMaxU) u = kMaxU;
+  if constexpr (kMaxU >= 4) if (u >= 4) return launch_w<W, 4>(a, grid, inv_w, s);
+  if constexpr (kMaxU >= 2) if (u >= 2) return launch_w<W, 2>(a, grid, inv_w, s);
   return launch_w<W, 1>(a, grid, inv_w, s);
 }
 
@@ -269,6 +273,7 @@ hipError_t launch_u(const ReduceArgs& a, dim3 grid, float inv_w, hipStream_t s) 
 
 hipError_t launch_ring_reduce(const ReduceArgs& a, hipStream_t s) {
   if (a.count == 0) return hipSuccess;
+  if (a.block != 256 && a.block != 512 && a.block != 1024) return hipErrorInvalidValue;
   uint32_t g = a.count;
   if (a.max_grid && g > a.max_grid) g = a.max_grid;
   const dim3 grid(g);
@@ -281,7 +286,7 @@ hipError_t launch_ring_reduce(const ReduceArgs& a, hipStream_t s) {
     default: break;
   }
 #define CARAMEL_ANY(BF, NT) \
-  hipLaunchKernelGGL((k_ring_reduce_any<BF, NT>), grid, dim3(kBlock), 0, s, a.tiles, a.rows, a.begin, a.count, a.world, inv_w)
+  hipLaunchKernelGGL((k_ring_reduce_any<BF, NT>), grid, dim3(a.block), 0, s, a.tiles, a.rows, a.begin, a.count, a.world, inv_w)
   if (a.bf16) {
     if (a.nontemporal) CARAMEL_ANY(true, true); else CARAMEL_ANY(true, false);
   } else {

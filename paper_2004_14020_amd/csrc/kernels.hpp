@@ -16,6 +16,7 @@ struct ReduceArgs {
   bool nontemporal;
   uint32_t unroll;    // vectors in flight per lane and worker: 1, 2 or 4 (0 = choose from W)
   uint32_t max_grid;  // 0 = one workgroup per tile
+  uint32_t block;     // lanes per workgroup: 256, 512 or 1024
 };
 
 struct CopyArgs {
