@@ -29,16 +29,17 @@ def parse_args():
     ap.add_argument("--workload", default="vgg16")
     ap.add_argument("--seed", type=int, default=0)
     ap.add_argument("--streams", type=int, default=None, help="override the workload's stream count")
-    ap.add_argument("--launch-mode", choices=["unit", "stream"], default=None)
+    ap.add_argument("--launch-mode", choices=["unit", "stream", "auto"], default=None)
     ap.add_argument("--batch-path", choices=["staged", "direct"], default=None)
     ap.add_argument("--tile-vecs", type=int, default=None)
     ap.add_argument("--max-grid", type=int, default=None)
     ap.add_argument("--nontemporal", type=int, default=None)
     ap.add_argument("--unroll", type=int, default=None)
+    ap.add_argument("--block", type=int, default=None)
     ap.add_argument("--device-fill", action="store_true",
                     help="fill the replicas on the device instead of uploading Philox samples")
     ap.add_argument("--no-cpu-baseline", action="store_true")
-    ap.add_argument("--cpu-repeats", type=int, default=5)
+    ap.add_argument("--cpu-repeats", type=int, default=21)
     return ap.parse_args()
 
 
@@ -83,11 +84,13 @@ def main() -> int:
                    align_bytes=wl.align_bytes, num_streams=streams)
     staged = args.batch_path == "staged"
     if args.launch_mode:
-        plan.set_option(cm.OPT_LAUNCH_MODE, cm.LAUNCH_PER_UNIT if args.launch_mode == "unit" else cm.LAUNCH_PER_STREAM)
+        plan.set_option(cm.OPT_LAUNCH_MODE, {"unit": cm.LAUNCH_PER_UNIT, "stream": cm.LAUNCH_PER_STREAM,
+                                             "auto": cm.LAUNCH_AUTO}[args.launch_mode])
     if args.batch_path:
         plan.set_option(cm.OPT_BATCH_PATH, cm.BATCH_STAGED if staged else cm.BATCH_DIRECT)
     for opt, val in ((cm.OPT_TILE_VECS, args.tile_vecs), (cm.OPT_MAX_GRID, args.max_grid),
-                     (cm.OPT_NONTEMPORAL, args.nontemporal), (cm.OPT_UNROLL, args.unroll)):
+                     (cm.OPT_NONTEMPORAL, args.nontemporal), (cm.OPT_UNROLL, args.unroll),
+                     (cm.OPT_BLOCK, args.block)):
         if val is not None:
             plan.set_option(opt, val)
 
@@ -103,7 +106,7 @@ def main() -> int:
     for _ in range(args.warmup):
         plan.allreduce(stream)
     torch.cuda.synchronize()
-    plan.profile(True)
+    plan.profile(1)
     torch.cuda.synchronize()
     t0 = time.perf_counter()
     for _ in range(args.steps):
@@ -111,29 +114,36 @@ def main() -> int:
     torch.cuda.synchronize()
     t1 = time.perf_counter()
     stats = plan.profile_read()
-    plan.profile(False)
+    plan.profile(0)
 
     ms_per_step = (t1 - t0) * 1e3 / args.steps
     alg_bytes = wl.algorithmic_bytes()
     gbs = alg_bytes / (ms_per_step * 1e-3) / 1e9
 
-    # dominant kernel: the ring-reduce kernel (in the default direct mode it is the only one)
-    red = stats[cm.K_REDUCE]
+    # Dominant kernel: k_ring_reduce (in the default direct mode it is the only kernel).  The
+    # library brackets everything each internal stream does in a call with one pair of HIP events
+    # recorded on that stream; launches of one stream run back to back, so a launch's average
+    # duration is the stream's busy time divided by its launches.  The two streams overlap in
+    # time (that is the pipeline), i.e. a launch shares the memory system with a launch of the
+    # other stream while it runs:
+    #   per_launch_achieved = algorithmic bytes of a launch / its average duration
+    #   achieved            = algorithmic bytes of a step / time from the first launch's start to
+    #                         the last launch's end (= per-launch figure x launches in flight)
+    red, seq = stats[cm.K_REDUCE], stats[cm.K_SEQUENCE]
     launches_per_step = red["launches"] / args.steps
-    avg_ms = red["total_ms"] / max(1, red["launches"])
-    span_ms = red["span_ms"] / max(1, red["calls"])
-    # algorithmic bytes of one launch: 2*W*s per element it reduces; all launches of a step
-    # together cover every element once
-    bytes_per_launch = alg_bytes / launches_per_step
-    achieved = bytes_per_launch / (avg_ms * 1e-3) / 1e9
+    avg_ms = seq["total_ms"] / max(1, red["launches"])
+    span_ms = seq["span_ms"] / max(1, seq["calls"])
+    bytes_per_launch = alg_bytes / launches_per_step       # 2*W*s per element the launch reduces
+    per_launch = bytes_per_launch / (avg_ms * 1e-3) / 1e9
+    achieved = alg_bytes / (span_ms * 1e-3) / 1e9
+    traffic = read_traffic(wl.name)
     roofline = {
         "bound": "hbm", "kernel": "k_ring_reduce", "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS,
-        "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": read_traffic(wl.name),
-        "launches_per_step": launches_per_step, "avg_launch_ms": round(avg_ms, 5),
-        "bytes_per_launch": bytes_per_launch,
-        # launches on the two internal streams overlap in time; the span is first start to last end
+        "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": traffic,
+        "launches_per_step": launches_per_step, "avg_launch_ms": round(avg_ms, 6),
+        "bytes_per_launch": round(bytes_per_launch), "per_launch_achieved": round(per_launch, 1),
+        "launches_in_flight": round(seq["total_ms"] / max(seq["span_ms"], 1e-9), 3),
         "step_span_ms": round(span_ms, 5),
-        "achieved_over_span": round(alg_bytes / (span_ms * 1e-3) / 1e9, 1) if span_ms > 0 else None,
     }
 
     cpu = None
@@ -165,7 +175,7 @@ def main() -> int:
                    "algorithmic_bytes": alg_bytes, "batch_threshold_bytes": wl.batch_threshold_bytes,
                    "split_mode": ["none", "fixed", "adaptive"][wl.split_mode], "split_bytes": wl.split_bytes,
                    "units": plan.counts()[0], "num_streams": streams,
-                   "launch_mode": args.launch_mode or "stream", "batch_path": args.batch_path or "direct"},
+                   "launch_mode": args.launch_mode or "auto", "batch_path": args.batch_path or "direct"},
         "roofline": roofline,
         "cpu_baseline": cpu,
     }

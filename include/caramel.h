@@ -161,8 +161,9 @@ int caramel_allreduce(caramel_plan* plan, void* stream);
 
 enum {
   /* How units map to kernel launches.  PER_UNIT: one launch per unit and stage (the literal
-   * pipeline).  PER_STREAM: consecutive units of one internal stream share launches through a
-   * descriptor table.  Default PER_STREAM. */
+   * pipeline).  PER_STREAM: all units of one internal stream share launches through a
+   * descriptor table.  AUTO (default): PER_UNIT with two streams, where the launches of one
+   * stream fill the gaps of the other; PER_STREAM with one. */
   CARAMEL_OPT_LAUNCH_MODE = 0,
   /* Batch units in caramel_allreduce.  STAGED: pack -> reduce -> unpack through fused_ws.
    * DIRECT: one gather-reduce-scatter kernel that reads member tensors and writes results back
@@ -180,7 +181,7 @@ enum {
   /* Lanes per workgroup of the reduce kernel: 256, 512 or 1024. */
   CARAMEL_OPT_BLOCK = 6
 };
-enum { CARAMEL_LAUNCH_PER_UNIT = 0, CARAMEL_LAUNCH_PER_STREAM = 1 };
+enum { CARAMEL_LAUNCH_PER_UNIT = 0, CARAMEL_LAUNCH_PER_STREAM = 1, CARAMEL_LAUNCH_AUTO = 2 };
 enum { CARAMEL_BATCH_STAGED = 0, CARAMEL_BATCH_DIRECT = 1 };
 
 /* Set a launch option.  Tile sizes take effect at the next caramel_bind (tables are rebuilt
@@ -188,13 +189,17 @@ enum { CARAMEL_BATCH_STAGED = 0, CARAMEL_BATCH_DIRECT = 1 };
  * EINVAL for an unknown option or a value out of range. */
 int caramel_plan_set_option(caramel_plan* plan, uint32_t option, uint64_t value);
 
-enum { CARAMEL_K_PACK = 0, CARAMEL_K_REDUCE = 1, CARAMEL_K_UNPACK = 2, CARAMEL_K_COUNT = 3 };
+enum { CARAMEL_K_PACK = 0, CARAMEL_K_REDUCE = 1, CARAMEL_K_UNPACK = 2, CARAMEL_K_SEQUENCE = 3, CARAMEL_K_COUNT = 4 };
 
-/* Per-kernel timing, measured with HIP events recorded on the stream each kernel is launched
- * on.  `launches`/`total_ms` accumulate over calls since profiling was switched on; `span_ms`
- * accumulates, per call, the time from the earliest start to the latest end of that kernel's
- * launches (launches on the two internal streams may overlap, and there may be gaps between
- * launches, so span and total differ in either direction). */
+/* Timing with HIP events recorded on the stream the work is launched on.
+ *   PACK / REDUCE / UNPACK  `launches` counts kernel launches; `total_ms` is the sum of their
+ *                           durations and is filled at level 2 only.
+ *   SEQUENCE                everything one stream does in one ring_reduce / allreduce call,
+ *                           from before its first launch to after its last: `launches` counts
+ *                           sequences, `total_ms` sums their durations (levels 1 and 2).
+ * `span_ms` accumulates, per call, the time from the earliest start to the latest end of the
+ * timed intervals of that kind (sequences on the two streams overlap, so for SEQUENCE the span
+ * is the duration of the whole call on the GPU); `calls` counts the calls that contributed. */
 typedef struct caramel_kernel_stat {
   uint64_t launches;
   double total_ms;
@@ -202,8 +207,11 @@ typedef struct caramel_kernel_stat {
   uint64_t calls;
 } caramel_kernel_stat;
 
-/* Switch event timing on (non-zero) or off and clear the statistics.  Requires a bound plan. */
-int caramel_profile(caramel_plan* plan, int enable);
+/* Set the timing level and clear the statistics.  0: off.  1: one event pair per stream and
+ * call (does not disturb back-to-back launches).  2: additionally one pair per kernel launch
+ * (exact per-kernel durations, but the events keep consecutive launches of a stream apart).
+ * Requires a bound plan. */
+int caramel_profile(caramel_plan* plan, int level);
 /* Synchronise the internal streams, fold pending event pairs into the statistics and copy
  * CARAMEL_K_COUNT records to `out`. */
 int caramel_profile_read(caramel_plan* plan, caramel_kernel_stat* out);

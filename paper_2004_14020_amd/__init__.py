@@ -4,8 +4,8 @@ The work is done by hand-written HIP kernels behind the C ABI declared in
 include/caramel.h; this package only marshals arguments (binding.py) and, in
 device.py, uses PyTorch to hold device memory and streams.
 """
-from .binding import (BATCH_DIRECT, BATCH_STAGED, BF16, F32, K_COUNT, K_PACK, K_REDUCE, K_UNPACK,
-                      KIND_BATCH, KIND_CHUNK, LAUNCH_PER_STREAM, LAUNCH_PER_UNIT, OPT_BATCH_PATH,
+from .binding import (BATCH_DIRECT, BATCH_STAGED, BF16, F32, K_COUNT, K_PACK, K_REDUCE, K_SEQUENCE, K_UNPACK,
+                      KIND_BATCH, KIND_CHUNK, LAUNCH_AUTO, LAUNCH_PER_STREAM, LAUNCH_PER_UNIT, OPT_BATCH_PATH,
                       OPT_BLOCK, OPT_LAUNCH_MODE, OPT_MAX_GRID, OPT_NONTEMPORAL, OPT_TILE_VECS, OPT_UNROLL,
                       SPLIT_ADAPTIVE, SPLIT_FIXED, SPLIT_NONE, CaramelError, Config, Entry, Plan, Unit, lib)
 
@@ -63,8 +63,8 @@ def caramel_allreduce(plan: Plan, stream: int = 0) -> None:
     plan.allreduce(stream)
 
 
-def caramel_profile(plan: Plan, enable: bool) -> None:
-    plan.profile(enable)
+def caramel_profile(plan: Plan, level: int) -> None:
+    plan.profile(level)
 
 
 def caramel_profile_read(plan: Plan):

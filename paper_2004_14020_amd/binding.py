@@ -18,9 +18,9 @@ F32, BF16 = 0, 1
 SPLIT_NONE, SPLIT_FIXED, SPLIT_ADAPTIVE = 0, 1, 2
 KIND_BATCH, KIND_CHUNK = 0, 1
 OPT_LAUNCH_MODE, OPT_BATCH_PATH, OPT_TILE_VECS, OPT_MAX_GRID, OPT_NONTEMPORAL, OPT_UNROLL, OPT_BLOCK = range(7)
-LAUNCH_PER_UNIT, LAUNCH_PER_STREAM = 0, 1
+LAUNCH_PER_UNIT, LAUNCH_PER_STREAM, LAUNCH_AUTO = 0, 1, 2
 BATCH_STAGED, BATCH_DIRECT = 0, 1
-K_PACK, K_REDUCE, K_UNPACK, K_COUNT = 0, 1, 2, 3
+K_PACK, K_REDUCE, K_UNPACK, K_SEQUENCE, K_COUNT = 0, 1, 2, 3, 4
 
 EXPORTS = (
     "caramel_plan_create", "caramel_plan_destroy", "caramel_plan_counts", "caramel_plan_units",
@@ -183,8 +183,8 @@ class Plan:
     def allreduce(self, stream: int = 0) -> None:
         _check(lib().caramel_allreduce(self._h, C.c_void_p(stream)))
 
-    def profile(self, enable: bool) -> None:
-        _check(lib().caramel_profile(self._h, 1 if enable else 0))
+    def profile(self, level: int) -> None:
+        _check(lib().caramel_profile(self._h, int(level)))
 
     def profile_read(self):
         buf = (KernelStat * K_COUNT)()

@@ -5,6 +5,7 @@
 #include <cstdarg>
 #include <cstdio>
 #include <cstring>
+#include <memory>
 #include <new>
 #include <string>
 #include <vector>
@@ -37,14 +38,14 @@ int fail(int code, const char* fmt, ...) {
   } while (0)
 
 struct Options {
-  uint32_t launch_mode = CARAMEL_LAUNCH_PER_STREAM;
+  uint32_t launch_mode = CARAMEL_LAUNCH_AUTO;
   uint32_t batch_path = CARAMEL_BATCH_DIRECT;
   uint32_t tile_vecs = 1024;
   uint32_t copy_vecs = 512;
   uint32_t max_grid = 0;
   uint32_t nontemporal = 1;
   uint32_t unroll = 0;
-  uint32_t block = 512;
+  uint32_t block = 1024;
 };
 
 struct TimedLaunch {
@@ -70,7 +71,7 @@ struct caramel_plan {
   hipEvent_t ev_fork = nullptr;
   hipEvent_t ev_join[2] = {nullptr, nullptr};
   // timing
-  bool profiling = false;
+  int profiling = 0;  // 0 off, 1 one event pair per stream sequence, 2 one pair per launch
   uint64_t call_no = 0;
   std::vector<TimedLaunch> pending;
   std::vector<hipEvent_t> spare;
@@ -123,7 +124,8 @@ hipEvent_t take_event(caramel_plan* p) {
   return e;
 }
 
-// Wraps one kernel launch in a pair of timing events on the launch stream when profiling.
+// Wraps a kernel launch (or a stream's whole sequence) in a pair of timing events on the
+// launch stream when profiling.
 struct Timed {
   caramel_plan* p;
   hipStream_t s;
@@ -131,6 +133,10 @@ struct Timed {
   bool on = false;
   Timed(caramel_plan* plan, int kind, hipStream_t stream) : p(plan), s(stream) {
     if (!p->profiling) return;
+    if (kind != CARAMEL_K_SEQUENCE) {
+      p->stats[kind].launches += 1;
+      if (p->profiling < 2) return;
+    }
     t.kind = kind;
     t.call = p->call_no;
     t.start = take_event(p);
@@ -224,7 +230,14 @@ int pipeline(caramel_plan* p, hipStream_t user, bool with_copies, bool direct) {
   const std::vector<Range>& unit_tiles = direct ? tt.direct_unit : tt.staged_unit;
   const Range* stream_tiles = direct ? tt.direct_stream : tt.staged_stream;
   const bool copies = with_copies && !direct;
-  if (p->opt.launch_mode == CARAMEL_LAUNCH_PER_STREAM) {
+  // one event pair around everything a stream does in this call
+  std::unique_ptr<Timed> seq[2];
+  if (p->profiling)
+    for (uint32_t s = 0; s < p->host.cfg.num_streams; ++s) seq[s].reset(new Timed(p, CARAMEL_K_SEQUENCE, lane[s]));
+  uint32_t mode = p->opt.launch_mode;
+  if (mode == CARAMEL_LAUNCH_AUTO)
+    mode = p->host.cfg.num_streams == 2 ? CARAMEL_LAUNCH_PER_UNIT : CARAMEL_LAUNCH_PER_STREAM;
+  if (mode == CARAMEL_LAUNCH_PER_STREAM) {
     for (uint32_t s = 0; s < p->host.cfg.num_streams && !rc; ++s) {
       if (copies) rc = run_copy(p, false, tt.copy_stream[s], lane[s]);
       if (!rc) rc = run_reduce(p, direct, stream_tiles[s], lane[s]);
@@ -238,6 +251,7 @@ int pipeline(caramel_plan* p, hipStream_t user, bool with_copies, bool direct) {
       if (!rc && copies) rc = run_copy(p, true, tt.copy_unit[u], s);
     }
   }
+  for (auto& q : seq) q.reset();
   // join even after a failed launch so the caller's stream stays ordered
   const int jc = join_streams(p, user);
   return rc ? rc : jc;
@@ -341,7 +355,7 @@ int caramel_plan_set_option(caramel_plan* p, uint32_t option, uint64_t value) {
   if (!p) return fail(CARAMEL_EINVAL, "plan is NULL");
   switch (option) {
     case CARAMEL_OPT_LAUNCH_MODE:
-      if (value > CARAMEL_LAUNCH_PER_STREAM) return fail(CARAMEL_EINVAL, "unknown launch mode");
+      if (value > CARAMEL_LAUNCH_AUTO) return fail(CARAMEL_EINVAL, "unknown launch mode");
       p->opt.launch_mode = uint32_t(value);
       return CARAMEL_OK;
     case CARAMEL_OPT_BATCH_PATH:
@@ -462,7 +476,7 @@ int caramel_profile(caramel_plan* p, int enable) {
     if (p->streams[s]) HIP_TRY(hipStreamSynchronize(p->streams[s]));
   drop_events(p);
   std::memset(p->stats, 0, sizeof p->stats);
-  p->profiling = enable != 0;
+  p->profiling = enable < 0 ? 0 : (enable > 2 ? 2 : enable);
   return CARAMEL_OK;
 }
 
@@ -485,7 +499,7 @@ int caramel_profile_read(caramel_plan* p, caramel_kernel_stat* out) {
       HIP_TRY(hipEventSynchronize(t.stop));
       float ms = 0.f;
       HIP_TRY(hipEventElapsedTime(&ms, t.start, t.stop));
-      p->stats[t.kind].launches += 1;
+      if (t.kind == CARAMEL_K_SEQUENCE) p->stats[t.kind].launches += 1;
       p->stats[t.kind].total_ms += ms;
       if (base) {
         float a = 0.f, b = 0.f;

@@ -210,16 +210,23 @@ def test_accuracy_bound_against_float64():
 def test_profile_counters():
     cfg = small_cfg(8, oracle.F32)
     elems = list(SMALL_ELEMS)
-    plan = lib_plan(cfg, elems, {cm.OPT_BATCH_PATH: cm.BATCH_STAGED})
+    plan = lib_plan(cfg, elems, {cm.OPT_BATCH_PATH: cm.BATCH_STAGED, cm.OPT_LAUNCH_MODE: cm.LAUNCH_PER_STREAM})
     dev = Replicas(plan, elems)
     dev.upload(make_inputs(cfg, elems, seed=3))
-    plan.profile(True)
-    for _ in range(3):
-        plan.allreduce()
-    st = plan.profile_read()
-    # one reduce launch per stream and call; pack/unpack only on streams that own batch units
-    assert st[cm.K_REDUCE]["launches"] == 6
-    assert st[cm.K_PACK]["launches"] == st[cm.K_UNPACK]["launches"] and st[cm.K_PACK]["launches"] in (3, 6)
-    assert st[cm.K_REDUCE]["calls"] == 3 and st[cm.K_REDUCE]["span_ms"] > 0 and st[cm.K_REDUCE]["total_ms"] > 0
-    plan.profile(False)
+    for level in (1, 2):
+        plan.profile(level)
+        for _ in range(3):
+            plan.allreduce()
+        st = plan.profile_read()
+        # one reduce launch per stream and call; pack/unpack only on streams that own batch units
+        assert st[cm.K_REDUCE]["launches"] == 6
+        assert st[cm.K_PACK]["launches"] == st[cm.K_UNPACK]["launches"] and st[cm.K_PACK]["launches"] in (3, 6)
+        seq = st[cm.K_SEQUENCE]
+        assert seq["launches"] == 6 and seq["calls"] == 3 and seq["total_ms"] > 0 and seq["span_ms"] > 0
+        if level == 2:
+            assert st[cm.K_REDUCE]["calls"] == 3 and st[cm.K_REDUCE]["total_ms"] > 0
+            assert st[cm.K_REDUCE]["total_ms"] <= seq["total_ms"]
+        else:
+            assert st[cm.K_REDUCE]["total_ms"] == 0
+    plan.profile(0)
     plan.close()
