@@ -39,6 +39,10 @@ def parse_args():
     ap.add_argument("--device-fill", action="store_true",
                     help="fill the replicas on the device instead of uploading Philox samples")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--calibrate", action="store_true",
+                    help="also run a plain in-place copy of known size (a W=1 reduction of one 1 GiB "
+                         "tensor, kernel k_ring_reduce_any) so that a counter run can scale "
+                         "FETCH_SIZE / WRITE_SIZE by what they read for it")
     ap.add_argument("--cpu-repeats", type=int, default=21)
     return ap.parse_args()
 
@@ -103,6 +107,16 @@ def main() -> int:
         dev.upload(grads)
 
     stream = torch.cuda.current_stream().cuda_stream
+    if args.calibrate:
+        n_cal = (1 << 30) // 4
+        cal = cm.Plan(1, [n_cal], num_streams=1)
+        buf = torch.zeros(n_cal, dtype=torch.float32, device="cuda:0")
+        cal.bind([[buf.data_ptr()]], None)
+        for _ in range(3):
+            cal.allreduce(stream)          # reads 1 GiB, writes 1 GiB
+        torch.cuda.synchronize()
+        cal.close()
+        del buf
     for _ in range(args.warmup):
         plan.allreduce(stream)
     torch.cuda.synchronize()
