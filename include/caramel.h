@@ -61,7 +61,9 @@ enum { CARAMEL_KIND_BATCH = 0, CARAMEL_KIND_CHUNK = 1 };
  *                         max_depth = 8.
  *   align_bytes           granule: batch members and ring segments start on multiples of it.
  *                         A power of two, >= 16 (one 128-bit vector).
- *   num_streams           1 or 2 internal streams; unit u runs on stream u mod num_streams.
+ *   num_streams           1 or 2; unit u belongs to stream u mod num_streams.  Stream 0 is the
+ *                         caller's stream, stream 1 an internal stream forked from and joined
+ *                         back to it with events.
  */
 typedef struct caramel_config {
   uint32_t world;
@@ -133,7 +135,7 @@ int caramel_plan_serialize(const caramel_plan* plan, void* buf, size_t* len);
  *   fused_ws  DEVICE workspace of world * fused_elems elements (replica w's fused buffer starts
  *             at element w * fused_elems); may be NULL when fused_elems == 0, or when only
  *             caramel_allreduce in its default (direct) mode is going to be used.
- * The library uploads its descriptor tables (synchronously) and creates its internal streams.
+ * The library uploads its descriptor tables (synchronously) and creates its internal stream.
  * May be called again to re-bind.  EINVAL: NULL/misaligned pointer.  EHIP: a HIP call failed. */
 int caramel_bind(caramel_plan* plan, void* const* grads, void* fused_ws);
 
@@ -145,9 +147,9 @@ int caramel_bind(caramel_plan* plan, void* const* grads, void* fused_ws);
  *                      planned offset; alignment padding is written as +0.0 (section 4.2).
  * caramel_ring_reduce  every unit, in place: batch units in fused_ws, chunk units directly in
  *                      tensor memory.  Ring reduce-scatter order, scale by 1/W, all-gather to
- *                      all W replicas (sections 2, 4.4).  Units run on the plan's internal
- *                      streams (unit u on stream u mod num_streams) between a fork from and a
- *                      join back to `stream`, both with events.
+ *                      all W replicas (sections 2, 4.4).  Units of plan stream 0 are queued on
+ *                      `stream`, units of plan stream 1 on the internal stream between a fork
+ *                      from and a join back to `stream`, both with events.
  * caramel_unpack       batch units: fused_ws -> member tensors of every replica.
  * caramel_allreduce    the whole path; afterwards every grads[w][t] holds the average, the same
  *                      bytes for every w, and identical to pack -> ring_reduce -> unpack.
@@ -163,7 +165,8 @@ enum {
   /* How units map to kernel launches.  PER_UNIT: one launch per unit and stage (the literal
    * pipeline).  PER_STREAM: all units of one internal stream share launches through a
    * descriptor table.  AUTO (default): PER_UNIT with two streams, where the launches of one
-   * stream fill the gaps of the other; PER_STREAM with one. */
+   * stream fill the gaps of the other, if the call is large enough to repay the fork and join
+   * (CARAMEL_OPT_PIPELINE_MIN_BYTES); otherwise PER_STREAM on the caller's stream. */
   CARAMEL_OPT_LAUNCH_MODE = 0,
   /* Batch units in caramel_allreduce.  STAGED: pack -> reduce -> unpack through fused_ws.
    * DIRECT: one gather-reduce-scatter kernel that reads member tensors and writes results back
@@ -179,7 +182,15 @@ enum {
   /* 16-byte vectors each lane keeps in flight per worker: 1, 2 or 4; 0 = chosen from W. */
   CARAMEL_OPT_UNROLL = 5,
   /* Lanes per workgroup of the reduce kernel: 256, 512 or 1024. */
-  CARAMEL_OPT_BLOCK = 6
+  CARAMEL_OPT_BLOCK = 6,
+  /* PER_UNIT launches only: consecutive units of one stream share a launch until it covers at
+   * least this many bytes per replica (0 = strictly one launch per unit).  The launch-side
+   * counterpart of the batching threshold: it amortises launch overhead over small units. */
+  CARAMEL_OPT_LAUNCH_MIN_BYTES = 7,
+  /* AUTO launch mode only: a call whose algorithmic bytes (2 * world * elements * element size)
+   * are below this value is not pipelined: it runs as one launch per stage on the caller's
+   * stream, with no fork or join.  Default 256 MiB. */
+  CARAMEL_OPT_PIPELINE_MIN_BYTES = 8
 };
 enum { CARAMEL_LAUNCH_PER_UNIT = 0, CARAMEL_LAUNCH_PER_STREAM = 1, CARAMEL_LAUNCH_AUTO = 2 };
 enum { CARAMEL_BATCH_STAGED = 0, CARAMEL_BATCH_DIRECT = 1 };

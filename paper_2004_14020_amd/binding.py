@@ -17,7 +17,8 @@ OK, EINVAL, ENOMEM, EHIP, ESTATE = 0, 1, 2, 3, 4
 F32, BF16 = 0, 1
 SPLIT_NONE, SPLIT_FIXED, SPLIT_ADAPTIVE = 0, 1, 2
 KIND_BATCH, KIND_CHUNK = 0, 1
-OPT_LAUNCH_MODE, OPT_BATCH_PATH, OPT_TILE_VECS, OPT_MAX_GRID, OPT_NONTEMPORAL, OPT_UNROLL, OPT_BLOCK = range(7)
+(OPT_LAUNCH_MODE, OPT_BATCH_PATH, OPT_TILE_VECS, OPT_MAX_GRID, OPT_NONTEMPORAL, OPT_UNROLL, OPT_BLOCK,
+ OPT_LAUNCH_MIN_BYTES, OPT_PIPELINE_MIN_BYTES) = range(9)
 LAUNCH_PER_UNIT, LAUNCH_PER_STREAM, LAUNCH_AUTO = 0, 1, 2
 BATCH_STAGED, BATCH_DIRECT = 0, 1
 K_PACK, K_REDUCE, K_UNPACK, K_SEQUENCE, K_COUNT = 0, 1, 2, 3, 4

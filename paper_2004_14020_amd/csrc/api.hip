@@ -46,6 +46,17 @@ struct Options {
   uint32_t nontemporal = 1;
   uint32_t unroll = 0;
   uint32_t block = 1024;
+  uint64_t launch_min_bytes = 4u << 20;
+  uint64_t pipeline_min_bytes = uint64_t(256) << 20;
+};
+
+// Fork/join events order work between streams of the same device; no timing, and no system-scope
+// fence (device scope is enough: every producer and consumer is a kernel on this GPU).
+constexpr unsigned kOrderOnly = hipEventDisableTiming | hipEventDisableSystemFence;
+
+struct LaunchGroup {
+  uint32_t stream, first_unit;
+  Range reduce, copy;
 };
 
 struct TimedLaunch {
@@ -63,6 +74,8 @@ struct caramel_plan {
   bool bound = false;
   bool has_ws = false;
   TileTables tt;
+  std::vector<LaunchGroup> groups[2];  // [0] staged tables, [1] direct tables
+  bool groups_stale[2] = {true, true};
   uint64_t* d_rows = nullptr;
   ReduceTile* d_staged = nullptr;
   ReduceTile* d_direct = nullptr;
@@ -120,7 +133,8 @@ hipEvent_t take_event(caramel_plan* p) {
     return e;
   }
   hipEvent_t e = nullptr;
-  if (hipEventCreate(&e) != hipSuccess) return nullptr;
+  // timing only: no system-scope fence, which would cost a cache write-back per record
+  if (hipEventCreateWithFlags(&e, hipEventDisableSystemFence) != hipSuccess) return nullptr;
   return e;
 }
 
@@ -195,66 +209,104 @@ int begin_call(caramel_plan* p, hipStream_t user) {
   return CARAMEL_OK;
 }
 
-// Internal streams start after everything queued on the caller's stream ...
-int fork_streams(caramel_plan* p, hipStream_t user, hipStream_t* lane) {
-  const uint32_t ns = p->host.cfg.num_streams;
-  if (ns == 1) {
-    lane[0] = user;
-    return CARAMEL_OK;
-  }
+// Stream 0 of the plan is the caller's stream itself; stream 1 is an internal stream that starts
+// after everything already queued on the caller's stream ...
+int fork_streams(caramel_plan* p, hipStream_t user, hipStream_t* lane, bool pipelined) {
+  lane[0] = lane[1] = user;
+  if (!pipelined) return CARAMEL_OK;
   HIP_TRY(hipEventRecord(p->ev_fork, user));
-  for (uint32_t s = 0; s < ns; ++s) {
-    HIP_TRY(hipStreamWaitEvent(p->streams[s], p->ev_fork, 0));
-    lane[s] = p->streams[s];
-  }
+  HIP_TRY(hipStreamWaitEvent(p->streams[1], p->ev_fork, 0));
+  lane[1] = p->streams[1];
   return CARAMEL_OK;
 }
 
-// ... and the caller's stream continues after both have drained.
-int join_streams(caramel_plan* p, hipStream_t user) {
-  const uint32_t ns = p->host.cfg.num_streams;
-  if (ns == 1) return CARAMEL_OK;
-  for (uint32_t s = 0; s < ns; ++s) {
-    HIP_TRY(hipEventRecord(p->ev_join[s], p->streams[s]));
-    HIP_TRY(hipStreamWaitEvent(user, p->ev_join[s], 0));
-  }
+// ... and the caller's stream continues after the internal stream has drained.
+int join_streams(caramel_plan* p, hipStream_t user, bool pipelined) {
+  if (!pipelined) return CARAMEL_OK;
+  HIP_TRY(hipEventRecord(p->ev_join[1], p->streams[1]));
+  HIP_TRY(hipStreamWaitEvent(user, p->ev_join[1], 0));
   return CARAMEL_OK;
+}
+
+// Consecutive units of one stream are launched together until the launch covers at least
+// `launch_min_bytes` per replica (PER_UNIT), or all together (PER_STREAM).  Their tiles are
+// adjacent in the tables, so a group is one tile range.  Groups are issued in the order of their
+// first unit, which alternates between the streams.
+// AUTO: the two-stream pipeline pays a fixed price for its fork and join (tens of microseconds
+// of cross-stream signalling), so it is used only when a call moves enough bytes to win that
+// back; smaller calls go out as one launch per stream on the caller's stream.
+bool use_pipeline(const caramel_plan* p) {
+  if (p->host.cfg.num_streams != 2) return false;
+  if (p->opt.launch_mode != CARAMEL_LAUNCH_AUTO) return true;
+  uint64_t elems = 0;
+  for (uint64_t e : p->host.tensor_elems) elems += e;
+  return 2 * uint64_t(p->host.cfg.world) * elems * p->host.elem_size() >= p->opt.pipeline_min_bytes;
+}
+
+const std::vector<LaunchGroup>& launch_groups(caramel_plan* p, bool direct) {
+  std::vector<LaunchGroup>& out = p->groups[direct ? 1 : 0];
+  if (!p->groups_stale[direct ? 1 : 0]) return out;
+  out.clear();
+  const TileTables& tt = p->tt;
+  const std::vector<Range>& unit_tiles = direct ? tt.direct_unit : tt.staged_unit;
+  uint32_t mode = p->opt.launch_mode;
+  if (mode == CARAMEL_LAUNCH_AUTO) mode = use_pipeline(p) ? CARAMEL_LAUNCH_PER_UNIT : CARAMEL_LAUNCH_PER_STREAM;
+  if (!use_pipeline(p) && p->host.cfg.num_streams == 2) {
+    // not pipelined: both plan streams run on the caller's stream, and since the tables hold
+    // stream 0's tiles followed by stream 1's, one launch per stage covers everything
+    const std::vector<ReduceTile>& all = direct ? tt.direct : tt.staged;
+    out.push_back(LaunchGroup{0, 0, Range{0, uint32_t(all.size())}, Range{0, uint32_t(tt.copy.size())}});
+    p->groups_stale[direct ? 1 : 0] = false;
+    return out;
+  }
+  const uint64_t es = p->host.elem_size();
+  for (uint32_t s = 0; s < p->host.cfg.num_streams; ++s) {
+    LaunchGroup g{};
+    uint64_t bytes = 0;
+    bool open = false;
+    for (uint32_t u : tt.stream_units[s]) {
+      if (!open) {
+        g = LaunchGroup{s, u, Range{unit_tiles[u].begin, 0}, Range{tt.copy_unit[u].begin, 0}};
+        bytes = 0;
+        open = true;
+      }
+      g.reduce.count += unit_tiles[u].count;
+      g.copy.count += tt.copy_unit[u].count;
+      bytes += p->host.units[u].elems * es;
+      if (mode == CARAMEL_LAUNCH_PER_UNIT && bytes >= p->opt.launch_min_bytes) {
+        out.push_back(g);
+        open = false;
+      }
+    }
+    if (open) out.push_back(g);
+  }
+  std::sort(out.begin(), out.end(), [](const LaunchGroup& a, const LaunchGroup& b) { return a.first_unit < b.first_unit; });
+  p->groups_stale[direct ? 1 : 0] = false;
+  return out;
 }
 
 // Shared body of caramel_ring_reduce (reduce only, staged tables) and caramel_allreduce.
 int pipeline(caramel_plan* p, hipStream_t user, bool with_copies, bool direct) {
   begin_call(p, user);
   hipStream_t lane[2] = {nullptr, nullptr};
-  int rc = fork_streams(p, user, lane);
+  const bool pipelined = use_pipeline(p);
+  int rc = fork_streams(p, user, lane, pipelined);
   if (rc) return rc;
-  const TileTables& tt = p->tt;
-  const std::vector<Range>& unit_tiles = direct ? tt.direct_unit : tt.staged_unit;
-  const Range* stream_tiles = direct ? tt.direct_stream : tt.staged_stream;
   const bool copies = with_copies && !direct;
   // one event pair around everything a stream does in this call
   std::unique_ptr<Timed> seq[2];
   if (p->profiling)
-    for (uint32_t s = 0; s < p->host.cfg.num_streams; ++s) seq[s].reset(new Timed(p, CARAMEL_K_SEQUENCE, lane[s]));
-  uint32_t mode = p->opt.launch_mode;
-  if (mode == CARAMEL_LAUNCH_AUTO)
-    mode = p->host.cfg.num_streams == 2 ? CARAMEL_LAUNCH_PER_UNIT : CARAMEL_LAUNCH_PER_STREAM;
-  if (mode == CARAMEL_LAUNCH_PER_STREAM) {
-    for (uint32_t s = 0; s < p->host.cfg.num_streams && !rc; ++s) {
-      if (copies) rc = run_copy(p, false, tt.copy_stream[s], lane[s]);
-      if (!rc) rc = run_reduce(p, direct, stream_tiles[s], lane[s]);
-      if (!rc && copies) rc = run_copy(p, true, tt.copy_stream[s], lane[s]);
-    }
-  } else {
-    for (uint32_t u = 0; u < p->host.units.size() && !rc; ++u) {
-      hipStream_t s = lane[p->host.units[u].stream];
-      if (copies) rc = run_copy(p, false, tt.copy_unit[u], s);
-      if (!rc) rc = run_reduce(p, direct, unit_tiles[u], s);
-      if (!rc && copies) rc = run_copy(p, true, tt.copy_unit[u], s);
-    }
+    for (uint32_t s = 0; s < (pipelined ? 2u : 1u); ++s) seq[s].reset(new Timed(p, CARAMEL_K_SEQUENCE, lane[s]));
+  for (const LaunchGroup& g : launch_groups(p, direct)) {
+    hipStream_t s = lane[g.stream];
+    if (copies) rc = run_copy(p, false, g.copy, s);
+    if (!rc) rc = run_reduce(p, direct, g.reduce, s);
+    if (!rc && copies) rc = run_copy(p, true, g.copy, s);
+    if (rc) break;
   }
   for (auto& q : seq) q.reset();
   // join even after a failed launch so the caller's stream stays ordered
-  const int jc = join_streams(p, user);
+  const int jc = join_streams(p, user, pipelined);
   return rc ? rc : jc;
 }
 
@@ -294,7 +346,7 @@ int caramel_plan_create(const caramel_config* cfg, const uint64_t* tensor_elems,
 
 void caramel_plan_destroy(caramel_plan* p) {
   if (!p) return;
-  if (p->bound || p->streams[0] || p->ev_fork) {
+  if (p->bound || p->streams[1] || p->ev_fork) {
     for (int s = 0; s < 2; ++s)
       if (p->streams[s]) (void)hipStreamSynchronize(p->streams[s]);
     drop_events(p);
@@ -358,6 +410,7 @@ int caramel_plan_set_option(caramel_plan* p, uint32_t option, uint64_t value) {
     case CARAMEL_OPT_LAUNCH_MODE:
       if (value > CARAMEL_LAUNCH_AUTO) return fail(CARAMEL_EINVAL, "unknown launch mode");
       p->opt.launch_mode = uint32_t(value);
+      p->groups_stale[0] = p->groups_stale[1] = true;
       return CARAMEL_OK;
     case CARAMEL_OPT_BATCH_PATH:
       if (value > CARAMEL_BATCH_DIRECT) return fail(CARAMEL_EINVAL, "unknown batch path");
@@ -377,6 +430,14 @@ int caramel_plan_set_option(caramel_plan* p, uint32_t option, uint64_t value) {
     case CARAMEL_OPT_UNROLL:
       if (value != 0 && value != 1 && value != 2 && value != 4) return fail(CARAMEL_EINVAL, "unroll must be 0, 1, 2 or 4");
       p->opt.unroll = uint32_t(value);
+      return CARAMEL_OK;
+    case CARAMEL_OPT_LAUNCH_MIN_BYTES:
+      p->opt.launch_min_bytes = value;
+      p->groups_stale[0] = p->groups_stale[1] = true;
+      return CARAMEL_OK;
+    case CARAMEL_OPT_PIPELINE_MIN_BYTES:
+      p->opt.pipeline_min_bytes = value;
+      p->groups_stale[0] = p->groups_stale[1] = true;
       return CARAMEL_OK;
     case CARAMEL_OPT_BLOCK:
       if (value != 256 && value != 512 && value != 1024) return fail(CARAMEL_EINVAL, "block must be 256, 512 or 1024");
@@ -420,6 +481,7 @@ int caramel_bind(caramel_plan* p, void* const* grads, void* fused_ws) {
   release_device(p);
 
   build_tiles(h, p->opt.tile_vecs, p->opt.copy_vecs, p->tt);
+  p->groups_stale[0] = p->groups_stale[1] = true;
   std::vector<uint64_t> rows((n + 1) * W, 0);
   for (uint32_t w = 0; w < W; ++w) {
     for (size_t t = 0; t < n; ++t) rows[t * W + w] = reinterpret_cast<uint64_t>(grads[w * n + t]);
@@ -433,12 +495,10 @@ int caramel_bind(caramel_plan* p, void* const* grads, void* fused_ws) {
     release_device(p);
     return rc;
   }
-  if (h.cfg.num_streams > 1 && !p->streams[0]) {
-    for (uint32_t s = 0; s < h.cfg.num_streams; ++s) {
-      HIP_TRY(hipStreamCreateWithFlags(&p->streams[s], hipStreamNonBlocking));
-      HIP_TRY(hipEventCreateWithFlags(&p->ev_join[s], hipEventDisableTiming));
-    }
-    HIP_TRY(hipEventCreateWithFlags(&p->ev_fork, hipEventDisableTiming));
+  if (h.cfg.num_streams > 1 && !p->streams[1]) {
+    HIP_TRY(hipStreamCreateWithFlags(&p->streams[1], hipStreamNonBlocking));
+    HIP_TRY(hipEventCreateWithFlags(&p->ev_join[1], kOrderOnly));
+    HIP_TRY(hipEventCreateWithFlags(&p->ev_fork, kOrderOnly));
   }
   p->has_ws = fused_ws != nullptr;
   p->bound = true;
