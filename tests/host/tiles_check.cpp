@@ -1,0 +1,174 @@
+// Host-only check of the planner and the tile tables, built with AddressSanitizer and UBSan.
+// For random configurations it verifies what the kernels rely on: every tile stays inside
+// its row, starts on a 16-byte vector, lies inside one ring segment with the right first
+// worker, and the tiles of a table cover every element exactly once.
+#include <algorithm>
+#include <cstdint>
+#include <cstdio>
+#include <cstdlib>
+#include <map>
+#include <random>
+#include <string>
+#include <vector>
+
+#include "plan.hpp"
+#include "tiles.hpp"
+
+using namespace caramel;
+
+static int fails = 0;
+#define CHECK(c)                                                        \
+  do {                                                                  \
+    if (!(c)) {                                                         \
+      std::printf("FAIL %s:%d  %s\n", __FILE__, __LINE__, #c);          \
+      if (++fails > 20) std::exit(1);                                   \
+    }                                                                   \
+  } while (0)
+
+static void check_case(const caramel_config& cfg, const std::vector<uint64_t>& elems, uint32_t tile_vecs,
+                       uint32_t copy_vecs) {
+  HostPlan p;
+  std::string why;
+  const int rc = build_host_plan(cfg, elems.data(), uint32_t(elems.size()), p, why);
+  CHECK(rc == CARAMEL_OK);
+  if (rc != CARAMEL_OK) return;
+  TileTables tt;
+  build_tiles(p, tile_vecs, copy_vecs, tt);
+  const uint64_t es = p.elem_size(), ve = 16 / es, W = cfg.world;
+  const uint32_t fused_row = uint32_t(elems.size());
+  auto row_elems = [&](uint32_t row) { return row == fused_row ? p.fused_elems : elems[row]; };
+
+  for (int table = 0; table < 2; ++table) {
+    const std::vector<ReduceTile>& tiles = table ? tt.direct : tt.staged;
+    const std::vector<Range>& per_unit = table ? tt.direct_unit : tt.staged_unit;
+    // coverage counters per row
+    std::map<uint32_t, std::vector<uint8_t>> seen;
+    uint64_t total_tiles = 0;
+    for (uint32_t u = 0; u < p.units.size(); ++u) {
+      const caramel_unit& un = p.units[u];
+      const uint64_t* seg = p.segments(u);
+      const Range r = per_unit[u];
+      CHECK(uint64_t(r.begin) + r.count <= tiles.size());
+      total_tiles += r.count;
+      for (uint32_t i = r.begin; i < r.begin + r.count; ++i) {
+        const ReduceTile& t = tiles[i];
+        CHECK(t.n_elems > 0 && t.n_elems <= uint64_t(tile_vecs) * ve);
+        CHECK(t.first < W);
+        CHECK(t.row <= fused_row);
+        const uint64_t e0 = uint64_t(t.vec_off) * ve, e1 = e0 + t.n_elems;
+        CHECK(e1 <= row_elems(t.row));
+        // ragged only at the very end of a tensor row (the fused row is whole granules)
+        if (t.n_elems % ve) CHECK(t.row != fused_row && e1 == elems[t.row]);
+        // position inside the unit -> segment -> first worker
+        uint64_t unit_pos = ~0ull;
+        if (un.kind == CARAMEL_KIND_CHUNK) {
+          const caramel_entry& e = p.entries[un.first_entry];
+          CHECK(t.row == e.tensor && e0 >= e.tensor_off && e1 <= e.tensor_off + e.elems);
+          unit_pos = e0 - e.tensor_off;
+        } else if (t.row == fused_row) {
+          CHECK(table == 0 && e0 >= un.fused_off && e1 <= un.fused_off + un.elems);
+          unit_pos = e0 - un.fused_off;
+        } else {
+          CHECK(table == 1);
+          bool found = false;
+          for (uint32_t k = 0; k < un.n_entries; ++k) {
+            const caramel_entry& e = p.entries[un.first_entry + k];
+            if (e.tensor == t.row) {
+              CHECK(e0 >= e.tensor_off && e1 <= e.tensor_off + e.elems);
+              unit_pos = e.unit_off + (e0 - e.tensor_off);
+              found = true;
+            }
+          }
+          CHECK(found);
+        }
+        uint32_t c = 0;
+        while (c + 1 < W && seg[c + 1] <= unit_pos) ++c;
+        CHECK(unit_pos >= seg[c] && unit_pos + t.n_elems <= seg[c + 1]);
+        CHECK(t.first == (c + 1) % W);
+        std::vector<uint8_t>& s = seen[t.row];
+        if (s.empty()) s.assign(row_elems(t.row), 0);
+        for (uint64_t e = e0; e < e1; ++e) {
+          CHECK(s[e] == 0);
+          s[e] = 1;
+        }
+      }
+    }
+    CHECK(total_tiles == tiles.size());
+    // tensors: every element exactly once, except members of batch units in the staged table
+    std::vector<bool> in_batch(elems.size(), false);
+    for (const caramel_entry& e : p.entries)
+      if (p.units[e.unit].kind == CARAMEL_KIND_BATCH) in_batch[e.tensor] = true;
+    for (uint32_t t = 0; t < elems.size(); ++t) {
+      const bool expect = table == 1 || !in_batch[t];
+      const std::vector<uint8_t>& s = seen[t];
+      if (!expect) {
+        CHECK(s.empty());
+        continue;
+      }
+      CHECK(s.size() == elems[t]);
+      CHECK(std::all_of(s.begin(), s.end(), [](uint8_t b) { return b == 1; }));
+    }
+    if (table == 0 && p.fused_elems) {
+      const std::vector<uint8_t>& s = seen[fused_row];
+      CHECK(s.size() == p.fused_elems && std::all_of(s.begin(), s.end(), [](uint8_t b) { return b == 1; }));
+    }
+    // stream ranges partition the table in order
+    uint32_t at = 0;
+    const Range* sr = table ? tt.direct_stream : tt.staged_stream;
+    for (uint32_t s = 0; s < cfg.num_streams; ++s) {
+      CHECK(sr[s].begin == at);
+      at += sr[s].count;
+    }
+    CHECK(at == tiles.size());
+  }
+
+  // copy tiles: members of batch units, with the zero padding that follows each member
+  std::vector<uint8_t> fused_seen(p.fused_elems, 0);
+  for (const CopyTile& t : tt.copy) {
+    CHECK(t.row < fused_row && t.n_elems > 0 && t.n_elems <= uint64_t(copy_vecs) * ve);
+    const uint64_t t0 = uint64_t(t.t_vec_off) * ve, f0 = uint64_t(t.f_vec_off) * ve;
+    CHECK(t0 + t.n_elems <= elems[t.row]);
+    CHECK(f0 + t.n_elems + t.n_zero <= p.fused_elems);
+    if (t.n_elems % ve) CHECK(t0 + t.n_elems == elems[t.row]);
+    for (uint64_t e = f0; e < f0 + t.n_elems + t.n_zero; ++e) {
+      CHECK(fused_seen[e] == 0);
+      fused_seen[e] = 1;
+    }
+  }
+  CHECK(std::all_of(fused_seen.begin(), fused_seen.end(), [](uint8_t b) { return b == 1; }));
+}
+
+int main() {
+  std::mt19937_64 rng(20041402);
+  auto pick = [&](std::initializer_list<uint64_t> xs) {
+    std::vector<uint64_t> v(xs);
+    return v[rng() % v.size()];
+  };
+  for (int it = 0; it < 600; ++it) {
+    caramel_config cfg{};
+    cfg.world = uint32_t(pick({1, 2, 3, 4, 5, 7, 8, 16, 33, 64}));
+    cfg.dtype = uint32_t(rng() % 2);
+    cfg.align_bytes = uint32_t(pick({16, 16, 32, 64, 256}));
+    cfg.batch_threshold_bytes = pick({0, 64, 256, 1024, 4096, 1000, 65536});
+    cfg.split_mode = uint32_t(rng() % 3);
+    cfg.max_depth = uint32_t(pick({1, 2, 8}));
+    cfg.split_bytes = cfg.split_mode ? pick({1, 2, 4, 16, 64}) * std::max<uint64_t>(cfg.align_bytes, 64) : 0;
+    cfg.num_streams = uint32_t(1 + rng() % 2);
+    std::vector<uint64_t> elems(1 + rng() % 14);
+    for (uint64_t& e : elems) e = pick({1, 2, 3, 5, 8, 17, 64, 100, 255, 256, 257, 1000, 4096, 5000, 70000});
+    check_case(cfg, elems, uint32_t(pick({64, 256, 1024, 4096})), uint32_t(pick({64, 512})));
+  }
+  // rejected configurations must not crash
+  HostPlan p;
+  std::string why;
+  caramel_config bad{};
+  uint64_t one = 1;
+  CHECK(build_host_plan(bad, &one, 1, p, why) == CARAMEL_EINVAL);
+  CHECK(build_host_plan(bad, nullptr, 1, p, why) == CARAMEL_EINVAL);
+  if (fails) {
+    std::printf("%d checks failed\n", fails);
+    return 1;
+  }
+  std::printf("tiles_check ok\n");
+  return 0;
+}
