@@ -1,0 +1,125 @@
+"""Do the pins bite?  Plausible mistakes are planted in a copy of the oracle's source (on the
+CPU only) and the pin tests are run against the damaged copy: for every mistake at least one
+pin must fail.  The undamaged oracle must pass all of them through the same harness."""
+import importlib
+import os
+import sys
+import types
+
+import pytest
+
+import oracle
+import oracle.aggregate
+import oracle.plan
+
+import test_oracle_aggregate as pins_agg
+import test_oracle_plan as pins_plan
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+PLAN_PINS = [
+    pins_plan.test_mlp_plan_matches_hand_enumeration,
+    lambda: pins_plan.test_invariants_random(100),
+    pins_plan.test_size_equal_to_threshold_is_large,
+    pins_plan.test_large_tensor_does_not_flush_open_batch,
+    pins_plan.test_adaptive_depth_grows_with_size_and_saturates,
+    pins_plan.test_fixed_split_vgg_fc1_is_98_exact_chunks,
+    pins_plan.test_workload_plan_shapes,
+    pins_plan.test_batching_off_gives_one_unit_per_tensor,
+]
+AGG_PINS = [
+    pins_agg.test_worked_examples,
+    lambda: pins_agg.test_formula_equals_message_passing_simulation(4),
+    lambda: pins_agg.test_formula_equals_message_passing_simulation(5),
+    lambda: pins_agg.test_integer_inputs_give_exact_mean(8, oracle.F32),
+    lambda: pins_agg.test_integer_inputs_give_exact_mean(4, oracle.BF16),
+    lambda: pins_agg.test_identical_replicas_reduce_to_the_input(16, oracle.BF16),
+    lambda: pins_agg.test_pack_then_unpack_is_identity_and_padding_is_zero(oracle.F32),
+    lambda: pins_agg.test_pack_then_unpack_is_identity_and_padding_is_zero(oracle.BF16),
+    pins_agg.test_pack_places_position_codes,
+    lambda: pins_agg.test_error_bound_against_float64("mlp", oracle.BF16),
+    pins_agg.test_bf16_rounding_is_nearest_even_by_definition,
+    pins_agg.test_bf16_widening_is_exact,
+]
+
+# (file, text to replace, replacement, what the mistake is)
+MUTATIONS = [
+    ("plan.py", "if t_bytes == 0 or n * s >= t_bytes:", "if t_bytes == 0 or n * s > t_bytes:", "equality with the threshold counted as small"),
+    ("plan.py", "        at = _align_up(open_elems, g)\n        open_batch.append", "        at = open_elems\n        open_batch.append", "members not aligned to granules"),
+    ("plan.py", "        if _align_up(open_elems, g) * s >= t_bytes:", "        if _align_up(open_elems, g) * s > 2 * t_bytes:", "batch sent too late"),
+    ("plan.py", "        at = _align_up(open_elems, g)\n", "        if open_batch and _align_up(open_elems, g) * s + n * s >= t_bytes:\n            emit(KIND_BATCH, open_batch, _align_up(open_elems, g))\n            open_batch, open_elems = [], 0\n        at = _align_up(open_elems, g)\n", "batch sent before the member that fills it"),
+    ("plan.py", "            off = 0\n            for piece in chunk_sizes(cfg, n):", "            if open_batch:\n                emit(KIND_BATCH, open_batch, _align_up(open_elems, g))\n                open_batch, open_elems = [], 0\n            off = 0\n            for piece in chunk_sizes(cfg, n):", "a large tensor flushes the open batch"),
+    ("plan.py", "        gran = c * base + min(c, rem)", "        gran = c * base + max(0, c - (w - rem))", "surplus granules given to the last owners"),
+    ("plan.py", "        depth = min(max(nbytes // cfg.split_bytes, 1), cfg.max_depth)", "        depth = min(max(-(-nbytes // cfg.split_bytes), 1), cfg.max_depth)", "depth rounded up"),
+    ("plan.py", "        depth = min(max(nbytes // cfg.split_bytes, 1), cfg.max_depth)", "        depth = max(nbytes // cfg.split_bytes, 1)", "depth not capped"),
+    ("plan.py", "        piece = cfg.split_bytes // s\n", "        piece = cfg.split_bytes\n", "chunk size in bytes used as elements"),
+    ("plan.py", "                          u % cfg.num_streams, ring_segments(cfg, n)))", "                          0, ring_segments(cfg, n)))", "every unit on stream 0"),
+    ("plan.py", "            fused_off = fused_elems\n", "            fused_off = 0\n", "fused offsets not accumulated"),
+    ("aggregate.py", "        acc = val(c + 1).copy()\n        for k in range(2, W + 1):\n            acc = acc + val(c + k)", "        acc = val(c).copy()\n        for k in range(1, W):\n            acc = acc + val(c + k)", "chain starts at the owner"),
+    ("aggregate.py", "            acc = acc + val(c + k)", "            acc = acc + val(c + 2 - k)", "ring walked in the other direction"),
+    ("aggregate.py", "        for k in range(2, W + 1):", "        for k in range(2, W):", "last term dropped"),
+    ("aggregate.py", "        y = acc * inv_w", "        y = acc", "no scaling"),
+    ("aggregate.py", "        y = acc * inv_w", "        y = acc / np.float32(W)", "division instead of multiplication by the rounded reciprocal"),
+    ("aggregate.py", "    lsb = (b >> np.uint64(16)) & np.uint64(1)", "    lsb = np.uint64(1)", "ties rounded away from zero"),
+    ("aggregate.py", "    r = ((b + np.uint64(0x7FFF) + lsb) >> np.uint64(16)).astype(np.uint16)", "    r = (b >> np.uint64(16)).astype(np.uint16)", "bf16 truncation instead of rounding"),
+    ("aggregate.py", "    return (bits.astype(np.uint32) << np.uint32(16)).view(np.float32)", "    return (bits.astype(np.uint32) << np.uint32(15)).view(np.float32)", "wrong widening shift"),
+    ("aggregate.py", "            region[...] = 0\n", "", "padding not cleared"),
+    ("aggregate.py", "                region[e.unit_off:e.unit_off + e.elems] = \\\n                    grads[w][e.tensor][e.tensor_off:e.tensor_off + e.elems]", "                region[e.unit_off:e.unit_off + e.elems] = \\\n                    grads[0][e.tensor][e.tensor_off:e.tensor_off + e.elems]", "pack reads worker 0 for every replica"),
+]
+
+
+def load_variant(fname, old, new):
+    """Both oracle modules re-executed from source under a private package name, one of them edited."""
+    pkg = types.ModuleType("oracle_variant")
+    pkg.__path__ = []
+    mods = {}
+    for name in ("plan.py", "aggregate.py", "ring_sim.py"):
+        with open(os.path.join(ROOT, "oracle", name)) as f:
+            src = f.read()
+        if name == fname:
+            assert src.count(old) == 1, f"mutation target not found exactly once in {name}: {old!r}"
+            src = src.replace(old, new)
+        mod = types.ModuleType("oracle_variant." + name[:-3])
+        mod.__package__ = "oracle_variant"
+        sys.modules[mod.__name__] = mod
+        sys.modules["oracle_variant"] = pkg
+        exec(compile(src, os.path.join("oracle_variant", name), "exec"), mod.__dict__)
+        mods[name[:-3]] = mod
+        setattr(pkg, name[:-3], mod)
+    return mods
+
+
+def install(monkeypatch, mods):
+    """Point every name the pin tests use at the variant."""
+    exported = {}
+    for mod in mods.values():
+        for k, v in vars(mod).items():
+            if not k.startswith("_") and callable(v) and getattr(v, "__module__", "").startswith("oracle_variant"):
+                exported[k] = v
+    for target in (oracle, oracle.plan, oracle.aggregate, pins_plan, pins_agg):
+        for k, v in exported.items():
+            if hasattr(target, k):
+                monkeypatch.setattr(target, k, v)
+
+
+def run_pins():
+    failed = []
+    for pin in PLAN_PINS + AGG_PINS:
+        try:
+            pin()
+        except AssertionError:
+            failed.append(pin)
+        except Exception:                      # a crash also counts as "noticed"
+            failed.append(pin)
+    return failed
+
+
+def test_harness_passes_on_the_undamaged_oracle(monkeypatch):
+    install(monkeypatch, load_variant(None, None, None))
+    assert run_pins() == []
+
+
+@pytest.mark.parametrize("fname,old,new,what", MUTATIONS, ids=[m[3] for m in MUTATIONS])
+def test_planted_mistake_is_caught(monkeypatch, fname, old, new, what):
+    install(monkeypatch, load_variant(fname, old, new))
+    assert run_pins(), f"no pin noticed: {what}"

@@ -172,9 +172,9 @@ def random_case(rng):
     return cfg, elems
 
 
-def test_invariants_random():
+def test_invariants_random(rounds=500):
     rng = random.Random(20041402)
-    for _ in range(500):
+    for _ in range(rounds):
         cfg, elems = random_case(rng)
         plan = build_plan(cfg, elems)
         check_invariants(cfg, elems, plan)
