@@ -7,7 +7,8 @@ benchmark's CPU-baseline leg import it; the library never does and shares no
 code with it.
 """
 from .plan import (BF16, F32, KIND_BATCH, KIND_CHUNK, SPLIT_ADAPTIVE, SPLIT_FIXED, SPLIT_NONE,
-                   Config, Entry, Plan, Unit, build_plan, chunk_sizes, ring_segments)
+                   Config, Entry, Plan, Unit, build_plan, chunk_sizes, fit_linear, ring_segments,
+                   threshold_from_model)
 from .aggregate import (abs_sum_f64, allreduce, bf16_to_f32, f32_to_bf16_rne, mean_f64, new_fused,
                         pack, reduce_unit, ring_reduce, unit_views, unpack)
 from .ring_sim import ring_allreduce_sim

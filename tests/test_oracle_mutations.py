@@ -46,9 +46,9 @@ AGG_PINS = [
 MUTATIONS = [
     ("plan.py", "if t_bytes == 0 or n * s >= t_bytes:", "if t_bytes == 0 or n * s > t_bytes:", "equality with the threshold counted as small"),
     ("plan.py", "        at = _align_up(open_elems, g)\n        open_batch.append", "        at = open_elems\n        open_batch.append", "members not aligned to granules"),
-    ("plan.py", "        if _align_up(open_elems, g) * s >= t_bytes:", "        if _align_up(open_elems, g) * s > 2 * t_bytes:", "batch sent too late"),
-    ("plan.py", "        at = _align_up(open_elems, g)\n", "        if open_batch and _align_up(open_elems, g) * s + n * s >= t_bytes:\n            emit(KIND_BATCH, open_batch, _align_up(open_elems, g))\n            open_batch, open_elems = [], 0\n        at = _align_up(open_elems, g)\n", "batch sent before the member that fills it"),
-    ("plan.py", "            off = 0\n            for piece in chunk_sizes(cfg, n):", "            if open_batch:\n                emit(KIND_BATCH, open_batch, _align_up(open_elems, g))\n                open_batch, open_elems = [], 0\n            off = 0\n            for piece in chunk_sizes(cfg, n):", "a large tensor flushes the open batch"),
+    ("plan.py", "        full = _align_up(open_elems, g) * s >= t_bytes", "        full = _align_up(open_elems, g) * s > 2 * t_bytes", "batch sent too late"),
+    ("plan.py", "        at = _align_up(open_elems, g)\n", "        if open_batch and _align_up(open_elems, g) * s + n * s >= t_bytes:\n            emit(KIND_BATCH, open_batch, _align_up(open_elems, g), now)\n            open_batch, open_elems = [], 0\n        at = _align_up(open_elems, g)\n", "batch sent before the member that fills it"),
+    ("plan.py", "            off = 0\n            for piece in chunk_sizes(cfg, n):", "            if open_batch:\n                emit(KIND_BATCH, open_batch, _align_up(open_elems, g), now)\n                open_batch, open_elems = [], 0\n            off = 0\n            for piece in chunk_sizes(cfg, n):", "a large tensor flushes the open batch"),
     ("plan.py", "        gran = c * base + min(c, rem)", "        gran = c * base + max(0, c - (w - rem))", "surplus granules given to the last owners"),
     ("plan.py", "        depth = min(max(nbytes // cfg.split_bytes, 1), cfg.max_depth)", "        depth = min(max(-(-nbytes // cfg.split_bytes), 1), cfg.max_depth)", "depth rounded up"),
     ("plan.py", "        depth = min(max(nbytes // cfg.split_bytes, 1), cfg.max_depth)", "        depth = max(nbytes // cfg.split_bytes, 1)", "depth not capped"),
