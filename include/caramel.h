@@ -109,6 +109,33 @@ typedef struct caramel_plan caramel_plan; /* opaque, owned by the library */
 int caramel_plan_create(const caramel_config* cfg, const uint64_t* tensor_elems, uint32_t n_tensors,
                         caramel_plan** out);
 
+/* Timing-aware batching (section 4.2: the open batch is transferred when its size exceeds the
+ * threshold "or if the transfers in the queue are done before the next parameter update").
+ *   ready_time  n_tensors expected update times, non-decreasing, any unit of time;
+ *   net_a/net_b transfer-time model of the aggregation: a transfer of d bytes takes
+ *               net_a + net_b * d (same time unit; both >= 0).
+ * Transfers are served one at a time in queue order.  After a small tensor has joined the open
+ * batch, the batch is sent if it has reached the threshold, or if everything queued so far will
+ * have finished by the next tensor's update time (waiting for more members would leave the
+ * network idle); what is still open after the last tensor is sent then.  Times are IEEE
+ * doubles: start = max(update time, end of the previous transfer), end = start +
+ * (net_a + net_b * bytes).  Everything else is as in caramel_plan_create.  EINVAL additionally
+ * for NULL or decreasing ready_time and negative or NaN coefficients. */
+int caramel_plan_create_timed(const caramel_config* cfg, const uint64_t* tensor_elems, uint32_t n_tensors,
+                              const double* ready_time, double net_a, double net_b, caramel_plan** out);
+/* Modelled schedule of a timing-aware plan: per unit, when it entered the queue, when its
+ * transfer starts and when it ends.  Any array may be NULL; `cap` entries each.  ESTATE if the
+ * plan was not made by caramel_plan_create_timed, EINVAL if cap is smaller than the unit count. */
+int caramel_plan_times(const caramel_plan* plan, double* enqueue, double* start, double* finish, uint32_t cap);
+
+/* Threshold choice of section 4.2.  caramel_net_model_fit: the line time = a + b * bytes through
+ * two measured (size, transfer time) pairs (the paper measures 64 B and 4 MB).
+ * caramel_threshold_estimate: the smallest size x >= 1 with f(2x) / (2 f(x)) > 0.8 for
+ * f(d) = a + b*d, i.e. the smallest integer above 1.5 a / b, decided in exact arithmetic.
+ * EINVAL: equal sizes; a < 0, b <= 0, non-finite values, or a result beyond 64 bits. */
+int caramel_net_model_fit(uint64_t bytes1, double time1, uint64_t bytes2, double time2, double* a, double* b);
+int caramel_threshold_estimate(double a, double b, uint64_t* threshold_bytes);
+
 /* Free host and device tables and internal streams/events.  NULL is allowed. */
 void caramel_plan_destroy(caramel_plan* plan);
 

@@ -7,12 +7,29 @@ device.py, uses PyTorch to hold device memory and streams.
 from .binding import (BATCH_DIRECT, BATCH_STAGED, BF16, F32, K_COUNT, K_PACK, K_REDUCE, K_SEQUENCE, K_UNPACK,
                       KIND_BATCH, KIND_CHUNK, LAUNCH_AUTO, LAUNCH_PER_STREAM, LAUNCH_PER_UNIT, OPT_BATCH_PATH,
                       OPT_BLOCK, OPT_LAUNCH_MIN_BYTES, OPT_LAUNCH_MODE, OPT_PIPELINE_MIN_BYTES, OPT_MAX_GRID, OPT_NONTEMPORAL, OPT_TILE_VECS, OPT_UNROLL,
-                      SPLIT_ADAPTIVE, SPLIT_FIXED, SPLIT_NONE, CaramelError, Config, Entry, Plan, Unit, lib)
+                      SPLIT_ADAPTIVE, SPLIT_FIXED, SPLIT_NONE, CaramelError, Config, Entry, Plan, Unit, lib,
+                      net_model_fit, threshold_estimate)
 
 
 # Functional spellings with the names of the C entry points.
 def caramel_plan_create(world, elems, **kw) -> Plan:
     return Plan(world, elems, **kw)
+
+
+def caramel_plan_create_timed(world, elems, ready_time, net_a, net_b, **kw) -> Plan:
+    return Plan(world, elems, ready_time=ready_time, net_a=net_a, net_b=net_b, **kw)
+
+
+def caramel_plan_times(plan: Plan):
+    return plan.times()
+
+
+def caramel_net_model_fit(bytes1, time1, bytes2, time2):
+    return net_model_fit(bytes1, time1, bytes2, time2)
+
+
+def caramel_threshold_estimate(a, b) -> int:
+    return threshold_estimate(a, b)
 
 
 def caramel_plan_destroy(plan: Plan) -> None:

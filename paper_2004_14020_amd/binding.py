@@ -24,7 +24,8 @@ BATCH_STAGED, BATCH_DIRECT = 0, 1
 K_PACK, K_REDUCE, K_UNPACK, K_SEQUENCE, K_COUNT = 0, 1, 2, 3, 4
 
 EXPORTS = (
-    "caramel_plan_create", "caramel_plan_destroy", "caramel_plan_counts", "caramel_plan_units",
+    "caramel_plan_create", "caramel_plan_create_timed", "caramel_plan_times", "caramel_net_model_fit",
+    "caramel_threshold_estimate", "caramel_plan_destroy", "caramel_plan_counts", "caramel_plan_units",
     "caramel_plan_entries", "caramel_plan_segments", "caramel_plan_serialize", "caramel_bind",
     "caramel_pack", "caramel_ring_reduce", "caramel_unpack", "caramel_allreduce",
     "caramel_plan_set_option", "caramel_profile", "caramel_profile_read", "caramel_last_error",
@@ -76,6 +77,12 @@ def lib() -> C.CDLL:
     L = C.CDLL(LIB_PATH)
     P = C.c_void_p
     L.caramel_plan_create.argtypes = [C.POINTER(Config), C.POINTER(C.c_uint64), C.c_uint32, C.POINTER(P)]
+    L.caramel_plan_create_timed.argtypes = [C.POINTER(Config), C.POINTER(C.c_uint64), C.c_uint32,
+                                            C.POINTER(C.c_double), C.c_double, C.c_double, C.POINTER(P)]
+    L.caramel_plan_times.argtypes = [P, C.POINTER(C.c_double), C.POINTER(C.c_double), C.POINTER(C.c_double), C.c_uint32]
+    L.caramel_net_model_fit.argtypes = [C.c_uint64, C.c_double, C.c_uint64, C.c_double,
+                                        C.POINTER(C.c_double), C.POINTER(C.c_double)]
+    L.caramel_threshold_estimate.argtypes = [C.c_double, C.c_double, C.POINTER(C.c_uint64)]
     L.caramel_plan_destroy.argtypes = [P]
     L.caramel_plan_destroy.restype = None
     L.caramel_plan_counts.argtypes = [P, C.POINTER(C.c_uint32), C.POINTER(C.c_uint32), C.POINTER(C.c_uint64)]
@@ -106,13 +113,21 @@ class Plan:
 
     def __init__(self, world: int, elems: Sequence[int], dtype: int = F32, batch_threshold_bytes: int = 0,
                  split_mode: int = SPLIT_NONE, split_bytes: int = 0, max_depth: int = 8,
-                 align_bytes: int = 16, num_streams: int = 2):
+                 align_bytes: int = 16, num_streams: int = 2, ready_time: Optional[Sequence[float]] = None,
+                 net_a: float = 0.0, net_b: float = 0.0):
         self._h = C.c_void_p()
         self.cfg = Config(world, dtype, batch_threshold_bytes, split_mode, max_depth, split_bytes,
                           align_bytes, num_streams)
         self.n_tensors = len(elems)
         arr = (C.c_uint64 * max(1, len(elems)))(*[int(e) for e in elems])
-        _check(lib().caramel_plan_create(C.byref(self.cfg), arr, len(elems), C.byref(self._h)))
+        if ready_time is None:
+            _check(lib().caramel_plan_create(C.byref(self.cfg), arr, len(elems), C.byref(self._h)))
+        else:
+            if len(ready_time) != len(elems):
+                raise ValueError("ready_time must have one entry per tensor")
+            rt = (C.c_double * max(1, len(elems)))(*[float(t) for t in ready_time])
+            _check(lib().caramel_plan_create_timed(C.byref(self.cfg), arr, len(elems), rt, float(net_a),
+                                                   float(net_b), C.byref(self._h)))
 
     # -- lifetime
     def close(self) -> None:
@@ -153,6 +168,13 @@ class Plan:
         _check(lib().caramel_plan_segments(self._h, unit, buf))
         return list(buf)
 
+    def times(self):
+        """(enqueue, start, finish) lists of a timing-aware plan."""
+        n = self.counts()[0]
+        bufs = [(C.c_double * max(1, n))() for _ in range(3)]
+        _check(lib().caramel_plan_times(self._h, bufs[0], bufs[1], bufs[2], n))
+        return tuple(list(b[:n]) for b in bufs)
+
     def serialize(self) -> bytes:
         n = C.c_size_t(0)
         _check(lib().caramel_plan_serialize(self._h, None, C.byref(n)))
@@ -191,3 +213,15 @@ class Plan:
         buf = (KernelStat * K_COUNT)()
         _check(lib().caramel_profile_read(self._h, buf))
         return [dict(launches=s.launches, total_ms=s.total_ms, span_ms=s.span_ms, calls=s.calls) for s in buf]
+
+
+def net_model_fit(bytes1: int, time1: float, bytes2: int, time2: float):
+    a, b = C.c_double(), C.c_double()
+    _check(lib().caramel_net_model_fit(bytes1, time1, bytes2, time2, C.byref(a), C.byref(b)))
+    return a.value, b.value
+
+
+def threshold_estimate(a: float, b: float) -> int:
+    out = C.c_uint64()
+    _check(lib().caramel_threshold_estimate(a, b, C.byref(out)))
+    return out.value

@@ -2,6 +2,7 @@
 #include <hip/hip_runtime.h>
 
 #include <algorithm>
+#include <cmath>
 #include <cstdarg>
 #include <cstdio>
 #include <cstring>
@@ -322,8 +323,55 @@ int need_bound(const caramel_plan* p, bool needs_ws) {
 
 extern "C" {
 
+namespace {
+int create_plan(const caramel_config* cfg, const uint64_t* tensor_elems, uint32_t n_tensors,
+                const double* ready_time, double net_a, double net_b, caramel_plan** out);
+}
+
 int caramel_plan_create(const caramel_config* cfg, const uint64_t* tensor_elems, uint32_t n_tensors,
                         caramel_plan** out) {
+  return create_plan(cfg, tensor_elems, n_tensors, nullptr, 0.0, 0.0, out);
+}
+
+int caramel_plan_create_timed(const caramel_config* cfg, const uint64_t* tensor_elems, uint32_t n_tensors,
+                              const double* ready_time, double net_a, double net_b, caramel_plan** out) {
+  if (!ready_time) return fail(CARAMEL_EINVAL, "ready_time is NULL");
+  return create_plan(cfg, tensor_elems, n_tensors, ready_time, net_a, net_b, out);
+}
+
+int caramel_plan_times(const caramel_plan* p, double* enqueue, double* start, double* finish, uint32_t cap) {
+  if (!p) return fail(CARAMEL_EINVAL, "plan is NULL");
+  const HostPlan& h = p->host;
+  if (h.start_time.size() != h.units.size()) return fail(CARAMEL_ESTATE, "not a timing-aware plan");
+  if (cap < h.units.size()) return fail(CARAMEL_EINVAL, "capacity %u < %zu units", cap, h.units.size());
+  if (enqueue) std::copy(h.enqueue_time.begin(), h.enqueue_time.end(), enqueue);
+  if (start) std::copy(h.start_time.begin(), h.start_time.end(), start);
+  if (finish) std::copy(h.finish_time.begin(), h.finish_time.end(), finish);
+  return CARAMEL_OK;
+}
+
+int caramel_net_model_fit(uint64_t bytes1, double time1, uint64_t bytes2, double time2, double* a, double* b) {
+  if (!a || !b) return fail(CARAMEL_EINVAL, "NULL argument");
+  if (bytes1 == bytes2) return fail(CARAMEL_EINVAL, "the two sizes must differ");
+  if (!std::isfinite(time1) || !std::isfinite(time2)) return fail(CARAMEL_EINVAL, "times must be finite");
+  const double slope = (time2 - time1) / (double(bytes2) - double(bytes1));
+  *b = slope;
+  *a = time1 - slope * double(bytes1);
+  return CARAMEL_OK;
+}
+
+int caramel_threshold_estimate(double a, double b, uint64_t* threshold_bytes) {
+  if (!threshold_bytes) return fail(CARAMEL_EINVAL, "NULL argument");
+  if (!threshold_from_model(a, b, *threshold_bytes))
+    return fail(CARAMEL_EINVAL, "need finite a >= 0, b > 0 and a threshold below 2^64");
+  return CARAMEL_OK;
+}
+
+}  // extern "C"
+
+namespace {
+int create_plan(const caramel_config* cfg, const uint64_t* tensor_elems, uint32_t n_tensors,
+                const double* ready_time, double net_a, double net_b, caramel_plan** out) {
   if (!cfg || !out) return fail(CARAMEL_EINVAL, "NULL argument");
   *out = nullptr;
   caramel_plan* p = new (std::nothrow) caramel_plan;
@@ -331,7 +379,7 @@ int caramel_plan_create(const caramel_config* cfg, const uint64_t* tensor_elems,
   std::string why;
   int rc;
   try {
-    rc = build_host_plan(*cfg, tensor_elems, n_tensors, p->host, why);
+    rc = build_host_plan(*cfg, tensor_elems, n_tensors, ready_time, net_a, net_b, p->host, why);
   } catch (const std::bad_alloc&) {
     delete p;
     return fail(CARAMEL_ENOMEM, "out of host memory");
@@ -343,6 +391,9 @@ int caramel_plan_create(const caramel_config* cfg, const uint64_t* tensor_elems,
   *out = p;
   return CARAMEL_OK;
 }
+}  // namespace
+
+extern "C" {
 
 void caramel_plan_destroy(caramel_plan* p) {
   if (!p) return;

@@ -10,6 +10,7 @@
 #include "plan.hpp"
 
 #include <algorithm>
+#include <cmath>
 #include <cstring>
 
 namespace caramel {
@@ -20,8 +21,13 @@ inline uint64_t ceil_div(uint64_t x, uint64_t m) { return (x + m - 1) / m; }
 
 class Queue {
  public:
-  Queue(const caramel_config& c, HostPlan& p)
-      : cfg_(c), plan_(p), es_(p.elem_size()), gran_(p.granule()) {}
+  Queue(const caramel_config& c, HostPlan& p, bool timed, double a, double b)
+      : cfg_(c), plan_(p), es_(p.elem_size()), gran_(p.granule()), timed_(timed), a_(a), b_(b) {}
+
+  // Update time of the parameter being visited (timing-aware plans).
+  void set_now(double t) { now_ = t; }
+  // When everything queued so far will have been transferred.
+  double free_at() const { return free_at_; }
 
   // A transfer that goes out on its own, possibly cut into chunks.
   void send_alone(uint32_t tensor, uint64_t elems) {
@@ -35,11 +41,14 @@ class Queue {
   }
 
   // A small parameter joins the open batch; the batch leaves once it is large enough.
-  void join_batch(uint32_t tensor, uint64_t elems) {
+  // Returns true if the batch is now large enough and has been sent.
+  bool join_batch(uint32_t tensor, uint64_t elems) {
     const uint64_t at = round_up(fill_, gran_);
     pending_.push_back(caramel_entry{tensor, 0, 0, at, elems});
     fill_ = at + elems;
-    if (round_up(fill_, gran_) * es_ >= cfg_.batch_threshold_bytes) flush();
+    if (round_up(fill_, gran_) * es_ < cfg_.batch_threshold_bytes) return false;
+    flush();
+    return true;
   }
 
   void flush() {
@@ -78,6 +87,14 @@ class Queue {
     u.elems = elems;
     u.fused_off = fused_off;
     plan_.units.push_back(u);
+    if (timed_) {
+      // one transfer at a time, in queue order
+      const double begin = now_ > free_at_ ? now_ : free_at_;
+      free_at_ = begin + (a_ + b_ * double(elems * es_));
+      plan_.enqueue_time.push_back(now_);
+      plan_.start_time.push_back(begin);
+      plan_.finish_time.push_back(free_at_);
+    }
     // ring segments: granules dealt out as evenly as possible, the surplus to the first owners
     const uint64_t W = cfg_.world;
     const uint64_t q = ceil_div(elems, gran_);
@@ -92,14 +109,17 @@ class Queue {
   const caramel_config& cfg_;
   HostPlan& plan_;
   const uint64_t es_, gran_;
+  const bool timed_;
+  const double a_, b_;
+  double now_ = 0.0, free_at_ = 0.0;
   std::vector<caramel_entry> pending_;
   uint64_t fill_ = 0;
 };
 
 }  // namespace
 
-int build_host_plan(const caramel_config& cfg, const uint64_t* elems, uint32_t n, HostPlan& out,
-                    std::string& why) {
+int build_host_plan(const caramel_config& cfg, const uint64_t* elems, uint32_t n, const double* ready_time,
+                    double net_a, double net_b, HostPlan& out, std::string& why) {
   auto bad = [&](const char* m) {
     why = m;
     return CARAMEL_EINVAL;
@@ -125,21 +145,63 @@ int build_host_plan(const caramel_config& cfg, const uint64_t* elems, uint32_t n
     if (elems[i] > max_elems) return bad("tensor larger than 64 GiB");
   }
 
+  const bool timed = ready_time != nullptr;
+  if (timed) {
+    if (!(net_a >= 0.0) || !(net_b >= 0.0)) return bad("network model coefficients must be non-negative");
+    for (uint32_t i = 0; i + 1 < n; ++i)
+      if (!(ready_time[i] <= ready_time[i + 1])) return bad("ready_time must be non-decreasing");
+    if (!(ready_time[n - 1] == ready_time[n - 1])) return bad("ready_time holds a NaN");
+  }
+
   out = HostPlan{};
   out.cfg = cfg;
   out.tensor_elems.assign(elems, elems + n);
-  Queue q(cfg, out);
+  Queue q(cfg, out, timed, net_a, net_b);
   for (uint32_t i = 0; i < n; ++i) {
+    if (timed) q.set_now(ready_time[i]);
     const bool large = cfg.batch_threshold_bytes == 0 || elems[i] * es >= cfg.batch_threshold_bytes;
-    if (large)
+    if (large) {
       q.send_alone(i, elems[i]);
-    else
-      q.join_batch(i, elems[i]);
+      continue;
+    }
+    const bool sent = q.join_batch(i, elems[i]);
+    // section 4.2: the batch also goes out if the queue will have drained before the next
+    // parameter is updated -- waiting for more members would leave the network idle
+    if (!sent && timed && i + 1 < n && q.free_at() <= ready_time[i + 1]) q.flush();
   }
   q.flush();
   if (out.fused_elems > max_elems) return bad("fused buffer larger than 64 GiB per replica");
   if (out.units.size() > 0xFFFFFFF0ull) return bad("too many units");
   return CARAMEL_OK;
+}
+
+bool threshold_from_model(double a, double b, uint64_t& out) {
+  if (!(a >= 0.0) || !(b > 0.0) || !std::isfinite(a) || !std::isfinite(b)) return false;
+  if (a == 0.0) {
+    out = 1;
+    return true;
+  }
+  // a = ma * 2^ea, b = mb * 2^eb with 53-bit integer mantissas; the condition
+  // (a + 2bx) / (2a + 2bx) > 4/5  <=>  2bx > 3a  <=>  x > 3 ma 2^(ea - eb - 1) / mb
+  int ea = 0, eb = 0;
+  const unsigned __int128 ma = (unsigned __int128)std::ldexp(std::frexp(a, &ea), 53);
+  const unsigned __int128 mb = (unsigned __int128)std::ldexp(std::frexp(b, &eb), 53);
+  const int d = ea - eb - 1;
+  unsigned __int128 num = 3 * ma, den = mb;
+  if (d >= 0) {
+    if (d > 70) return false;  // far beyond 2^64
+    num <<= d;
+  } else {
+    if (-d > 70) {             // 3a / 2b is below 1
+      out = 1;
+      return true;
+    }
+    den <<= -d;
+  }
+  const unsigned __int128 x = num / den + 1;
+  if (x >> 64) return false;
+  out = uint64_t(x);
+  return true;
 }
 
 namespace {

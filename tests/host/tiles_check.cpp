@@ -29,7 +29,7 @@ static void check_case(const caramel_config& cfg, const std::vector<uint64_t>& e
                        uint32_t copy_vecs) {
   HostPlan p;
   std::string why;
-  const int rc = build_host_plan(cfg, elems.data(), uint32_t(elems.size()), p, why);
+  const int rc = build_host_plan(cfg, elems.data(), uint32_t(elems.size()), nullptr, 0.0, 0.0, p, why);
   CHECK(rc == CARAMEL_OK);
   if (rc != CARAMEL_OK) return;
   TileTables tt;
@@ -163,8 +163,8 @@ int main() {
   std::string why;
   caramel_config bad{};
   uint64_t one = 1;
-  CHECK(build_host_plan(bad, &one, 1, p, why) == CARAMEL_EINVAL);
-  CHECK(build_host_plan(bad, nullptr, 1, p, why) == CARAMEL_EINVAL);
+  CHECK(build_host_plan(bad, &one, 1, nullptr, 0.0, 0.0, p, why) == CARAMEL_EINVAL);
+  CHECK(build_host_plan(bad, nullptr, 1, nullptr, 0.0, 0.0, p, why) == CARAMEL_EINVAL);
   if (fails) {
     std::printf("%d checks failed\n", fails);
     return 1;

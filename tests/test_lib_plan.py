@@ -130,3 +130,66 @@ def test_bind_rejects_bad_pointers_before_any_device_call():
     with pytest.raises(cm.CaramelError) as ei:
         p.bind(good, 0x10020)                                    # workspace overlaps a tensor
     assert ei.value.status == binding.EINVAL
+
+
+# ------------------------------------------------------------------ section 4.2 extras
+def test_timed_plan_equals_oracle():
+    rng = random.Random(77)
+    for _ in range(300):
+        elems = [rng.choice([1, 3, 8, 17, 64, 100, 255, 256, 257, 1000, 5000, 70000]) for _ in range(rng.randint(1, 14))]
+        cfg = oracle.Config(rng.choice([1, 2, 8, 16]), rng.choice([oracle.F32, oracle.BF16]),
+                            rng.choice([256, 1024, 4096]), rng.choice([oracle.SPLIT_NONE, oracle.SPLIT_FIXED]), 8,
+                            4096, 16, rng.choice([1, 2]))
+        times = sorted(rng.random() * 50 for _ in elems)
+        a, b = rng.choice([0.0, 0.5, 5.0, 1e9]), rng.choice([0.0, 0.001, 0.01])
+        ref = oracle.build_plan(cfg, elems, times, a, b)
+        got = cm.Plan(cfg.world, elems, dtype=cfg.dtype, batch_threshold_bytes=cfg.batch_threshold_bytes,
+                      split_mode=cfg.split_mode, split_bytes=cfg.split_bytes, max_depth=cfg.max_depth,
+                      align_bytes=cfg.align_bytes, num_streams=cfg.num_streams, ready_time=times, net_a=a, net_b=b)
+        assert got.counts() == (len(ref.units), len(ref.entries), ref.fused_elems)
+        for u, r in zip(got.units(), ref.units):
+            assert (u.kind, u.stream, u.first_entry, u.n_entries, u.elems, u.fused_off) == \
+                   (r.kind, r.stream, r.first_entry, r.n_entries, r.elems, r.fused_off)
+        for e, r in zip(got.entries(), ref.entries):
+            assert (e.tensor, e.unit, e.tensor_off, e.unit_off, e.elems) == \
+                   (r.tensor, r.unit, r.tensor_off, r.unit_off, r.elems)
+        enq, start, fin = got.times()
+        assert enq == ref.enqueue_time and start == ref.start_time and fin == ref.finish_time   # same doubles
+        got.close()
+
+
+def test_timed_plan_argument_errors():
+    for kw in (dict(ready_time=[1.0, 0.5], net_a=1.0, net_b=1.0), dict(ready_time=[0.0, 1.0], net_a=-1.0, net_b=1.0),
+               dict(ready_time=[0.0, float("nan")], net_a=1.0, net_b=1.0)):
+        with pytest.raises(cm.CaramelError) as ei:
+            cm.Plan(2, [10, 10], batch_threshold_bytes=1024, **kw)
+        assert ei.value.status == binding.EINVAL
+    p = cm.Plan(2, [10, 10], batch_threshold_bytes=1024)
+    with pytest.raises(cm.CaramelError) as ei:
+        p.times()
+    assert ei.value.status == binding.ESTATE
+
+
+def test_threshold_estimate_equals_oracle():
+    rng = random.Random(5)
+    cases = [(40.0, 0.5), (0.0, 1.0), (1e-300, 1.0), (1e300, 1e-3), (3.0, 0.25), (7.0, 3.0)]
+    cases += [(rng.random() * 10 ** rng.randint(-3, 6), rng.random() * 10 ** rng.randint(-6, 2) + 1e-12) for _ in range(500)]
+    for a, b in cases:
+        want = oracle.threshold_from_model(a, b)
+        if want >= 1 << 64:
+            with pytest.raises(cm.CaramelError):
+                cm.threshold_estimate(a, b)
+        else:
+            assert cm.threshold_estimate(a, b) == want, (a, b)
+    assert cm.threshold_estimate(40.0, 0.5) == 121
+    for a, b in ((-1.0, 1.0), (1.0, 0.0), (float("inf"), 1.0), (1.0, float("nan"))):
+        with pytest.raises(cm.CaramelError):
+            cm.threshold_estimate(a, b)
+
+
+def test_net_model_fit():
+    a, b = cm.net_model_fit(64, 50.0 + 64 * 0.002, 4 << 20, 50.0 + (4 << 20) * 0.002)
+    fa, fb = oracle.fit_linear(64, 50.0 + 64 * 0.002, 4 << 20, 50.0 + (4 << 20) * 0.002)
+    assert a == pytest.approx(float(fa), rel=1e-9) and b == pytest.approx(float(fb), rel=1e-12)
+    with pytest.raises(cm.CaramelError):
+        cm.net_model_fit(64, 1.0, 64, 2.0)
