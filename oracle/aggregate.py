@@ -20,6 +20,17 @@ element of segment c
 
 with worker indices mod W.  bf16 inputs are widened exactly, all partial sums
 stay in fp32, and y is rounded once, to nearest-even, on the way out.
+
+Other patterns (paper sections 2 and 6.3 name them; only the order of the
+additions differs, the segments, scaling and all-gather are the same):
+
+* halving-doubling (recursive vector halving with distance doubling): in step k
+  worker r exchanges one half of its current range with worker r XOR 2^k and adds
+  what it receives to what it kept.  Every element therefore ends up as the
+  balanced pairwise tree  ((x0+x1)+(x2+x3)) + ((x4+x5)+(x6+x7)) ...  whatever
+  segment it lies in (fp addition is commutative, so who adds to whom is immaterial).
+* shuffle: the owner of a slice receives that slice from every worker and sums the
+  W pieces in worker order, x0 + x1 + ... + x(W-1), again the same for every slice.
 """
 from __future__ import annotations
 
@@ -27,7 +38,7 @@ from typing import List
 
 import numpy as np
 
-from .plan import BF16, F32, KIND_BATCH, Plan
+from .plan import (BF16, F32, KIND_BATCH, PATTERN_HALVING_DOUBLING, PATTERN_RING, PATTERN_SHUFFLE, Plan)
 
 
 # ---------------------------------------------------------------- bf16 <-> fp32
@@ -86,8 +97,8 @@ def unpack(plan: Plan, grads: List[List[np.ndarray]], fused: np.ndarray) -> None
 
 
 # ---------------------------------------------------------------- ring aggregation
-def reduce_unit(xs: List[np.ndarray], seg_start: List[int], dtype: int) -> None:
-    """Ring reduce-scatter + scale + all-gather of one unit, in place.
+def reduce_unit(xs: List[np.ndarray], seg_start: List[int], dtype: int, pattern: int = PATTERN_RING) -> None:
+    """Reduce-scatter + scale + all-gather of one unit, in place.
     xs[w] is worker w's view of the unit; seg_start has W+1 element offsets."""
     W = len(xs)
     inv_w = np.float32(1.0) / np.float32(W)
@@ -100,9 +111,21 @@ def reduce_unit(xs: List[np.ndarray], seg_start: List[int], dtype: int) -> None:
             v = xs[w % W][a:b]
             return bf16_to_f32(v) if dtype == BF16 else v
 
-        acc = val(c + 1).copy()
-        for k in range(2, W + 1):
-            acc = acc + val(c + k)          # fp32 + fp32 -> fp32, one rounding
+        if pattern == PATTERN_RING:
+            acc = val(c + 1).copy()
+            for k in range(2, W + 1):
+                acc = acc + val(c + k)          # fp32 + fp32 -> fp32, one rounding
+        elif pattern == PATTERN_SHUFFLE:
+            acc = val(0).copy()
+            for w in range(1, W):
+                acc = acc + val(w)
+        elif pattern == PATTERN_HALVING_DOUBLING:
+            part = [val(w) for w in range(W)]
+            while len(part) > 1:                # neighbours first, then pairs of pairs, ...
+                part = [part[i] + part[i + 1] for i in range(0, len(part), 2)]
+            acc = part[0]
+        else:
+            raise ValueError("pattern")
         y = acc * inv_w
         out = f32_to_bf16_rne(y) if dtype == BF16 else y
         for w in range(W):
@@ -119,7 +142,7 @@ def unit_views(plan: Plan, u, grads, fused) -> List[np.ndarray]:
 def ring_reduce(plan: Plan, grads: List[List[np.ndarray]], fused: np.ndarray) -> None:
     """All units: batch units on the fused buffers, chunk units on tensor memory."""
     for u in plan.units:
-        reduce_unit(unit_views(plan, u, grads, fused), u.seg_start, plan.cfg.dtype)
+        reduce_unit(unit_views(plan, u, grads, fused), u.seg_start, plan.cfg.dtype, plan.cfg.pattern)
 
 
 def allreduce(plan: Plan, grads: List[List[np.ndarray]], fused: np.ndarray = None) -> None:

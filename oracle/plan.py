@@ -42,6 +42,7 @@ from typing import List, Sequence
 F32, BF16 = 0, 1
 SPLIT_NONE, SPLIT_FIXED, SPLIT_ADAPTIVE = 0, 1, 2
 KIND_BATCH, KIND_CHUNK = 0, 1
+PATTERN_RING, PATTERN_HALVING_DOUBLING, PATTERN_SHUFFLE = 0, 1, 2
 
 
 @dataclass(frozen=True)
@@ -54,6 +55,7 @@ class Config:
     split_bytes: int = 0
     align_bytes: int = 16
     num_streams: int = 2
+    pattern: int = PATTERN_RING
 
     @property
     def elem_size(self) -> int:
@@ -151,6 +153,10 @@ def validate(cfg: Config, elems: Sequence[int]) -> None:
             raise ValueError("split_bytes must be a positive multiple of align_bytes")
     if cfg.split_mode == SPLIT_ADAPTIVE and cfg.max_depth < 1:
         raise ValueError("max_depth")
+    if cfg.pattern not in (PATTERN_RING, PATTERN_HALVING_DOUBLING, PATTERN_SHUFFLE):
+        raise ValueError("pattern")
+    if cfg.pattern == PATTERN_HALVING_DOUBLING and cfg.world not in (1, 2, 4, 8, 16):
+        raise ValueError("halving-doubling needs a power-of-two world of at most 16")
     if len(elems) == 0:
         raise ValueError("no tensors")
     if any(e <= 0 for e in elems):

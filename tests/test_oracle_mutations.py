@@ -13,7 +13,9 @@ import oracle.aggregate
 import oracle.plan
 
 import test_oracle_aggregate as pins_agg
+import test_oracle_patterns as pins_pat
 import test_oracle_plan as pins_plan
+import test_oracle_timed as pins_timed
 
 ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
 
@@ -40,6 +42,13 @@ AGG_PINS = [
     lambda: pins_agg.test_error_bound_against_float64("mlp", oracle.BF16),
     pins_agg.test_bf16_rounding_is_nearest_even_by_definition,
     pins_agg.test_bf16_widening_is_exact,
+    pins_pat.test_worked_example_values,
+    lambda: pins_pat.test_halving_doubling_formula_equals_protocol_simulation(8),
+    lambda: pins_pat.test_shuffle_formula_equals_protocol_simulation(5),
+    pins_timed.test_hand_walked_example,
+    pins_timed.test_an_infinitely_fast_network_never_batches,
+    pins_timed.test_schedule_invariants,
+    pins_timed.test_threshold_by_brute_force_scan_and_closed_form,
 ]
 
 # (file, text to replace, replacement, what the mistake is)
@@ -55,9 +64,14 @@ MUTATIONS = [
     ("plan.py", "        piece = cfg.split_bytes // s\n", "        piece = cfg.split_bytes\n", "chunk size in bytes used as elements"),
     ("plan.py", "                          u % cfg.num_streams, ring_segments(cfg, n)))", "                          0, ring_segments(cfg, n)))", "every unit on stream 0"),
     ("plan.py", "            fused_off = fused_elems\n", "            fused_off = 0\n", "fused offsets not accumulated"),
-    ("aggregate.py", "        acc = val(c + 1).copy()\n        for k in range(2, W + 1):\n            acc = acc + val(c + k)", "        acc = val(c).copy()\n        for k in range(1, W):\n            acc = acc + val(c + k)", "chain starts at the owner"),
-    ("aggregate.py", "            acc = acc + val(c + k)", "            acc = acc + val(c + 2 - k)", "ring walked in the other direction"),
-    ("aggregate.py", "        for k in range(2, W + 1):", "        for k in range(2, W):", "last term dropped"),
+    ("aggregate.py", "            acc = val(c + 1).copy()\n            for k in range(2, W + 1):\n                acc = acc + val(c + k)", "            acc = val(c).copy()\n            for k in range(1, W):\n                acc = acc + val(c + k)", "chain starts at the owner"),
+    ("aggregate.py", "                acc = acc + val(c + k)", "                acc = acc + val(c + 2 - k)", "ring walked in the other direction"),
+    ("aggregate.py", "            for k in range(2, W + 1):", "            for k in range(2, W):", "last term dropped"),
+    ("aggregate.py", "                part = [part[i] + part[i + 1] for i in range(0, len(part), 2)]", "                h = len(part) // 2\n                part = [part[i] + part[i + h] for i in range(h)]", "halving-doubling pairs the far partner first"),
+    ("aggregate.py", "            acc = val(0).copy()\n            for w in range(1, W):\n                acc = acc + val(w)", "            acc = val(c).copy()\n            for w in range(1, W):\n                acc = acc + val(c + w)", "shuffle sums starting from the owner"),
+    ("plan.py", "        idle_ahead = timed and t + 1 < len(elems) and free_at <= float(ready_time[t + 1])", "        idle_ahead = timed and t + 1 < len(elems) and free_at <= now", "idle test against the current update time"),
+    ("plan.py", "            begin = max(now, free_at)", "            begin = now", "transfers overlap instead of queueing"),
+    ("plan.py", "    x = (3 * a) // (2 * b) + 1", "    x = -((-3 * a) // (2 * b))", "threshold at the ratio instead of past it"),
     ("aggregate.py", "        y = acc * inv_w", "        y = acc", "no scaling"),
     ("aggregate.py", "        y = acc * inv_w", "        y = acc / np.float32(W)", "division instead of multiplication by the rounded reciprocal"),
     ("aggregate.py", "    lsb = (b >> np.uint64(16)) & np.uint64(1)", "    lsb = np.uint64(1)", "ties rounded away from zero"),
@@ -96,7 +110,7 @@ def install(monkeypatch, mods):
         for k, v in vars(mod).items():
             if not k.startswith("_") and callable(v) and getattr(v, "__module__", "").startswith("oracle_variant"):
                 exported[k] = v
-    for target in (oracle, oracle.plan, oracle.aggregate, pins_plan, pins_agg):
+    for target in (oracle, oracle.plan, oracle.aggregate, pins_plan, pins_agg, pins_pat, pins_timed):
         for k, v in exported.items():
             if hasattr(target, k):
                 monkeypatch.setattr(target, k, v)
