@@ -46,6 +46,7 @@ enum { CARAMEL_OK = 0, CARAMEL_EINVAL = 1, CARAMEL_ENOMEM = 2, CARAMEL_EHIP = 3,
 enum { CARAMEL_F32 = 0, CARAMEL_BF16 = 1 };
 enum { CARAMEL_SPLIT_NONE = 0, CARAMEL_SPLIT_FIXED = 1, CARAMEL_SPLIT_ADAPTIVE = 2 };
 enum { CARAMEL_KIND_BATCH = 0, CARAMEL_KIND_CHUNK = 1 };
+enum { CARAMEL_PATTERN_RING = 0, CARAMEL_PATTERN_HALVING_DOUBLING = 1, CARAMEL_PATTERN_SHUFFLE = 2 };
 
 /* Plan parameters.
  *   world                 W >= 1 replicas (at most CARAMEL_MAX_WORLD).
@@ -64,6 +65,13 @@ enum { CARAMEL_KIND_BATCH = 0, CARAMEL_KIND_CHUNK = 1 };
  *   num_streams           1 or 2; unit u belongs to stream u mod num_streams.  Stream 0 is the
  *                         caller's stream, stream 1 an internal stream forked from and joined
  *                         back to it with events.
+ *   pattern               decentralised aggregation pattern (sections 2 and 6.3); it fixes the
+ *                         order of the fp32 additions, everything else is the same.
+ *                         RING: segment c is summed x[c+1] + x[c+2] + ... + x[c] (indices mod W).
+ *                         HALVING_DOUBLING (recursive vector halving, distance doubling; W in
+ *                         {1,2,4,8,16}): the balanced tree ((x0+x1)+(x2+x3)) + ((x4+x5)+(x6+x7)) ...
+ *                         SHUFFLE (the owner of a slice receives it from every worker): x0 + x1 +
+ *                         ... + x(W-1) in worker order.
  */
 typedef struct caramel_config {
   uint32_t world;
@@ -74,6 +82,8 @@ typedef struct caramel_config {
   uint64_t split_bytes;
   uint32_t align_bytes;
   uint32_t num_streams;
+  uint32_t pattern;
+  uint32_t reserved; /* must be 0 */
 } caramel_config;
 
 #define CARAMEL_MAX_WORLD 64u
@@ -105,7 +115,8 @@ typedef struct caramel_plan caramel_plan; /* opaque, owned by the library */
  * order (ascending expected update time, section 4.2).  *out receives a new plan.
  * EINVAL: NULL argument, n_tensors == 0, a zero-element tensor, world out of range, unknown
  * dtype or split mode, align_bytes not a power of two >= 16, split_bytes not a positive
- * multiple of align_bytes when splitting, num_streams not 1 or 2, max_depth == 0 (ADAPTIVE). */
+ * multiple of align_bytes when splitting, num_streams not 1 or 2, max_depth == 0 (ADAPTIVE),
+ * unknown pattern, HALVING_DOUBLING with another world size, reserved != 0. */
 int caramel_plan_create(const caramel_config* cfg, const uint64_t* tensor_elems, uint32_t n_tensors,
                         caramel_plan** out);
 

@@ -17,6 +17,7 @@ OK, EINVAL, ENOMEM, EHIP, ESTATE = 0, 1, 2, 3, 4
 F32, BF16 = 0, 1
 SPLIT_NONE, SPLIT_FIXED, SPLIT_ADAPTIVE = 0, 1, 2
 KIND_BATCH, KIND_CHUNK = 0, 1
+PATTERN_RING, PATTERN_HALVING_DOUBLING, PATTERN_SHUFFLE = 0, 1, 2
 (OPT_LAUNCH_MODE, OPT_BATCH_PATH, OPT_TILE_VECS, OPT_MAX_GRID, OPT_NONTEMPORAL, OPT_UNROLL, OPT_BLOCK,
  OPT_LAUNCH_MIN_BYTES, OPT_PIPELINE_MIN_BYTES) = range(9)
 LAUNCH_PER_UNIT, LAUNCH_PER_STREAM, LAUNCH_AUTO = 0, 1, 2
@@ -36,7 +37,8 @@ EXPORTS = (
 class Config(C.Structure):
     _fields_ = [("world", C.c_uint32), ("dtype", C.c_uint32), ("batch_threshold_bytes", C.c_uint64),
                 ("split_mode", C.c_uint32), ("max_depth", C.c_uint32), ("split_bytes", C.c_uint64),
-                ("align_bytes", C.c_uint32), ("num_streams", C.c_uint32)]
+                ("align_bytes", C.c_uint32), ("num_streams", C.c_uint32), ("pattern", C.c_uint32),
+                ("reserved", C.c_uint32)]
 
 
 class Unit(C.Structure):
@@ -114,10 +116,10 @@ class Plan:
     def __init__(self, world: int, elems: Sequence[int], dtype: int = F32, batch_threshold_bytes: int = 0,
                  split_mode: int = SPLIT_NONE, split_bytes: int = 0, max_depth: int = 8,
                  align_bytes: int = 16, num_streams: int = 2, ready_time: Optional[Sequence[float]] = None,
-                 net_a: float = 0.0, net_b: float = 0.0):
+                 net_a: float = 0.0, net_b: float = 0.0, pattern: int = PATTERN_RING):
         self._h = C.c_void_p()
         self.cfg = Config(world, dtype, batch_threshold_bytes, split_mode, max_depth, split_bytes,
-                          align_bytes, num_streams)
+                          align_bytes, num_streams, pattern, 0)
         self.n_tensors = len(elems)
         arr = (C.c_uint64 * max(1, len(elems)))(*[int(e) for e in elems])
         if ready_time is None:

@@ -176,6 +176,7 @@ int run_reduce(caramel_plan* p, bool direct, Range r, hipStream_t s) {
   a.world = p->host.cfg.world;
   a.bf16 = p->host.cfg.dtype == CARAMEL_BF16;
   a.nontemporal = p->opt.nontemporal != 0;
+  a.tree = p->host.cfg.pattern == CARAMEL_PATTERN_HALVING_DOUBLING;
   // by default a workgroup takes its tile in one go: vectors per lane = tile / workgroup size
   a.unroll = p->opt.unroll ? p->opt.unroll : std::max(1u, p->opt.tile_vecs / p->opt.block);
   a.max_grid = p->opt.max_grid;

@@ -89,12 +89,54 @@ struct Chain {
   }
 };
 
+// Sum of the W vectors x[0..W-1] in the order of the pattern, scaled and converted back.
+// Chain: ((x0 + x1) + x2) + ...   Tree: neighbours first, then pairs of pairs, ...
+template <int W, bool BF16, bool TREE>
+__device__ __forceinline__ u32x4 combine(const u32x4 (&x)[W], float inv_w) {
+  if constexpr (!TREE) {
+    Chain<BF16> c;
+    c.start(x[0]);
+#pragma unroll
+    for (int k = 1; k < W; ++k) c.add(x[k]);
+    return c.finish(inv_w);
+  } else {
+    Chain<BF16> part[W];
+#pragma unroll
+    for (int k = 0; k < W; ++k) part[k].start(x[k]);
+#pragma unroll
+    for (int s = 1; s < W; s *= 2)
+#pragma unroll
+      for (int i = 0; i + s < W; i += 2 * s) {
+        part[i].a = part[i].a + part[i + s].a;
+        if constexpr (BF16) part[i].b = part[i].b + part[i + s].b;
+      }
+    return part[0].finish(inv_w);
+  }
+}
+
+// Same for one scalar element per worker.
+template <int W, bool TREE>
+__device__ __forceinline__ float combine_scalar(float (&v)[W], float inv_w) {
+  if constexpr (!TREE) {
+    float acc = v[0];
+#pragma unroll
+    for (int k = 1; k < W; ++k) acc = acc + v[k];
+    return acc * inv_w;
+  } else {
+#pragma unroll
+    for (int s = 1; s < W; s *= 2)
+#pragma unroll
+      for (int i = 0; i + s < W; i += 2 * s) v[i] = v[i] + v[i + s];
+    return v[0] * inv_w;
+  }
+}
+
 __device__ __forceinline__ float widen(uint16_t h) { return __uint_as_float(uint32_t(h) << 16); }
 
 // ------------------------------------------------------------------------------------------
 // W known at compile time: all W loads of a vector (times U vectors) are issued before the
 // first add, so each lane keeps W*U 128-bit requests in flight.
-template <int W, int U, bool BF16, bool NT>
+template <int W, int U, bool BF16, bool NT, bool TREE>
 __global__ void __launch_bounds__(kMaxBlock)
 k_ring_reduce(const ReduceTile* __restrict__ tiles, const uint64_t* __restrict__ rows, uint32_t begin,
               uint32_t count, float inv_w) {
@@ -121,11 +163,7 @@ k_ring_reduce(const ReduceTile* __restrict__ tiles, const uint64_t* __restrict__
       __builtin_amdgcn_sched_barrier(0);  // keep all loads ahead of the arithmetic
 #pragma unroll
       for (int u = 0; u < U; ++u) {
-        Chain<BF16> c;
-        c.start(x[u][0]);
-#pragma unroll
-        for (int k = 1; k < W; ++k) c.add(x[u][k]);
-        const u32x4 y = c.finish(inv_w);
+        const u32x4 y = combine<W, BF16, TREE>(x[u], inv_w);
 #pragma unroll
         for (int k = 0; k < W; ++k) st<NT>(at(p[k], (v + u * B) * 16u), y);
       }
@@ -135,11 +173,7 @@ k_ring_reduce(const ReduceTile* __restrict__ tiles, const uint64_t* __restrict__
 #pragma unroll
       for (int k = 0; k < W; ++k) x[k] = ld<NT>(at(p[k], v * 16u));
       __builtin_amdgcn_sched_barrier(0);
-      Chain<BF16> c;
-      c.start(x[0]);
-#pragma unroll
-      for (int k = 1; k < W; ++k) c.add(x[k]);
-      const u32x4 y = c.finish(inv_w);
+      const u32x4 y = combine<W, BF16, TREE>(x, inv_w);
 #pragma unroll
       for (int k = 0; k < W; ++k) st<NT>(at(p[k], v * 16u), y);
     }
@@ -147,18 +181,17 @@ k_ring_reduce(const ReduceTile* __restrict__ tiles, const uint64_t* __restrict__
     const uint32_t rem = tl.n_elems - nvec * VE;
     if (threadIdx.x < rem) {
       const uint32_t e = nvec * VE + threadIdx.x;
+      float v[W];
       if constexpr (BF16) {
-        float acc = widen(reinterpret_cast<gu16_ptr>(p[0])[e]);
 #pragma unroll
-        for (int k = 1; k < W; ++k) acc = acc + widen(reinterpret_cast<gu16_ptr>(p[k])[e]);
-        const uint16_t y = uint16_t(bf16_rne(acc * inv_w));
+        for (int k = 0; k < W; ++k) v[k] = widen(reinterpret_cast<gu16_ptr>(p[k])[e]);
+        const uint16_t y = uint16_t(bf16_rne(combine_scalar<W, TREE>(v, inv_w)));
 #pragma unroll
         for (int k = 0; k < W; ++k) reinterpret_cast<gu16_ptr>(p[k])[e] = y;
       } else {
-        float acc = reinterpret_cast<gf32_ptr>(p[0])[e];
 #pragma unroll
-        for (int k = 1; k < W; ++k) acc = acc + reinterpret_cast<gf32_ptr>(p[k])[e];
-        const float y = acc * inv_w;
+        for (int k = 0; k < W; ++k) v[k] = reinterpret_cast<gf32_ptr>(p[k])[e];
+        const float y = combine_scalar<W, TREE>(v, inv_w);
 #pragma unroll
         for (int k = 0; k < W; ++k) reinterpret_cast<gf32_ptr>(p[k])[e] = y;
       }
@@ -247,13 +280,16 @@ k_copy(const CopyTile* __restrict__ tiles, const uint64_t* __restrict__ rows, ui
 
 template <int W, int U>
 hipError_t launch_w(const ReduceArgs& a, dim3 grid, float inv_w, hipStream_t s) {
-#define CARAMEL_GO(BF, NT) \
-  hipLaunchKernelGGL((k_ring_reduce<W, U, BF, NT>), grid, dim3(a.block), 0, s, a.tiles, a.rows, a.begin, a.count, inv_w)
+#define CARAMEL_GO(BF, NT, TR) \
+  hipLaunchKernelGGL((k_ring_reduce<W, U, BF, NT, TR>), grid, dim3(a.block), 0, s, a.tiles, a.rows, a.begin, a.count, inv_w)
+#define CARAMEL_GO2(BF, NT) \
+  do { if (a.tree) CARAMEL_GO(BF, NT, true); else CARAMEL_GO(BF, NT, false); } while (0)
   if (a.bf16) {
-    if (a.nontemporal) CARAMEL_GO(true, true); else CARAMEL_GO(true, false);
+    if (a.nontemporal) CARAMEL_GO2(true, true); else CARAMEL_GO2(true, false);
   } else {
-    if (a.nontemporal) CARAMEL_GO(false, true); else CARAMEL_GO(false, false);
+    if (a.nontemporal) CARAMEL_GO2(false, true); else CARAMEL_GO2(false, false);
   }
+#undef CARAMEL_GO2
 #undef CARAMEL_GO
   return hipGetLastError();
 }
@@ -285,6 +321,8 @@ hipError_t launch_ring_reduce(const ReduceArgs& a, hipStream_t s) {
     case 16: return launch_u<16>(a, grid, inv_w, s);
     default: break;
   }
+  // the loop kernel adds as a chain; a tree over one worker is the same thing
+  if (a.tree && a.world != 1) return hipErrorInvalidValue;
 #define CARAMEL_ANY(BF, NT) \
   hipLaunchKernelGGL((k_ring_reduce_any<BF, NT>), grid, dim3(a.block), 0, s, a.tiles, a.rows, a.begin, a.count, a.world, inv_w)
   if (a.bf16) {

@@ -14,6 +14,7 @@ struct ReduceArgs {
   uint32_t world;
   bool bf16;
   bool nontemporal;
+  bool tree;          // add as a balanced pairwise tree (halving-doubling) instead of a chain
   uint32_t unroll;    // vectors in flight per lane and worker: 1, 2 or 4 (0 = choose from W)
   uint32_t max_grid;  // 0 = one workgroup per tile
   uint32_t block;     // lanes per workgroup: 256, 512 or 1024

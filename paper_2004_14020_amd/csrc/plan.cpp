@@ -137,6 +137,13 @@ int build_host_plan(const caramel_config& cfg, const uint64_t* elems, uint32_t n
       return bad("split_bytes must be a positive multiple of align_bytes");
     if (cfg.split_mode == CARAMEL_SPLIT_ADAPTIVE && cfg.max_depth == 0) return bad("max_depth is 0");
   }
+  if (cfg.pattern > CARAMEL_PATTERN_SHUFFLE) return bad("unknown pattern");
+  if (cfg.reserved != 0) return bad("reserved field must be 0");
+  if (cfg.pattern == CARAMEL_PATTERN_HALVING_DOUBLING) {
+    const uint32_t w = cfg.world;
+    if (!(w == 1 || w == 2 || w == 4 || w == 8 || w == 16))
+      return bad("halving-doubling needs a world of 1, 2, 4, 8 or 16");
+  }
   const uint64_t es = cfg.dtype == CARAMEL_F32 ? 4 : 2;
   // 32-bit offsets in units of 16 bytes address at most 64 GiB inside one tensor
   const uint64_t max_elems = (uint64_t(1) << 36) / es - a;
@@ -223,6 +230,7 @@ std::vector<uint8_t> serialize(const HostPlan& p) {
   put<uint64_t>(b, p.cfg.split_bytes);
   put<uint32_t>(b, p.cfg.align_bytes);
   put<uint32_t>(b, p.cfg.num_streams);
+  put<uint32_t>(b, p.cfg.pattern);
   put<uint32_t>(b, uint32_t(p.tensor_elems.size()));
   put<uint32_t>(b, uint32_t(p.units.size()));
   put<uint32_t>(b, uint32_t(p.entries.size()));

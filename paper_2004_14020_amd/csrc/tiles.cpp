@@ -49,7 +49,9 @@ void build_tiles(const HostPlan& p, uint32_t tile_vecs, uint32_t copy_vecs, Tile
       for (uint32_t c = 0; c < W; ++c) {
         const uint64_t a = seg[c], b = seg[c + 1];
         if (a == b) continue;
-        const uint32_t first = (c + 1) % W;
+        // ring: the chain of segment c starts at worker c+1; the other patterns add in an
+        // order that does not depend on the segment and read the workers from 0
+        const uint32_t first = p.cfg.pattern == CARAMEL_PATTERN_RING ? (c + 1) % W : 0;
         if (u.kind == CARAMEL_KIND_CHUNK) {
           cut_run(out.staged, ent[0].tensor, first, ent[0].tensor_off + a, b - a, ve, tile_elems);
           cut_run(out.direct, ent[0].tensor, first, ent[0].tensor_off + a, b - a, ve, tile_elems);

@@ -14,7 +14,7 @@ namespace caramel {
 // segment, so the chain of workers is the same for every lane.
 struct ReduceTile {
   uint32_t row;      // pointer row
-  uint32_t first;    // worker whose value starts the chain: (segment + 1) mod W
+  uint32_t first;    // worker whose value is read first: (segment + 1) mod W for the ring, else 0
   uint32_t vec_off;  // offset of the run inside the row, in 16-byte vectors
   uint32_t n_elems;  // elements in the run; only a run that ends a tensor may be ragged
 };

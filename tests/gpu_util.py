@@ -12,7 +12,7 @@ from workloads import gradients
 def lib_plan(cfg: oracle.Config, elems, opts: dict = None) -> cm.Plan:
     p = cm.Plan(cfg.world, elems, dtype=cfg.dtype, batch_threshold_bytes=cfg.batch_threshold_bytes,
                 split_mode=cfg.split_mode, split_bytes=cfg.split_bytes, max_depth=cfg.max_depth,
-                align_bytes=cfg.align_bytes, num_streams=cfg.num_streams)
+                align_bytes=cfg.align_bytes, num_streams=cfg.num_streams, pattern=cfg.pattern)
     for k, v in (opts or {}).items():
         p.set_option(k, v)
     return p

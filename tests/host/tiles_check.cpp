@@ -84,7 +84,7 @@ static void check_case(const caramel_config& cfg, const std::vector<uint64_t>& e
         uint32_t c = 0;
         while (c + 1 < W && seg[c + 1] <= unit_pos) ++c;
         CHECK(unit_pos >= seg[c] && unit_pos + t.n_elems <= seg[c + 1]);
-        CHECK(t.first == (c + 1) % W);
+        CHECK(t.first == (cfg.pattern == CARAMEL_PATTERN_RING ? (c + 1) % W : 0));
         std::vector<uint8_t>& s = seen[t.row];
         if (s.empty()) s.assign(row_elems(t.row), 0);
         for (uint64_t e = e0; e < e1; ++e) {
@@ -154,6 +154,8 @@ int main() {
     cfg.max_depth = uint32_t(pick({1, 2, 8}));
     cfg.split_bytes = cfg.split_mode ? pick({1, 2, 4, 16, 64}) * std::max<uint64_t>(cfg.align_bytes, 64) : 0;
     cfg.num_streams = uint32_t(1 + rng() % 2);
+    cfg.pattern = uint32_t(rng() % 3);
+    if (cfg.pattern == CARAMEL_PATTERN_HALVING_DOUBLING) cfg.world = uint32_t(pick({1, 2, 4, 8, 16}));
     std::vector<uint64_t> elems(1 + rng() % 14);
     for (uint64_t& e : elems) e = pick({1, 2, 3, 5, 8, 17, 64, 100, 255, 256, 257, 1000, 4096, 5000, 70000});
     check_case(cfg, elems, uint32_t(pick({64, 256, 1024, 4096})), uint32_t(pick({64, 512})));

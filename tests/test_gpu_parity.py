@@ -232,3 +232,70 @@ def test_profile_counters():
             assert st[cm.K_REDUCE]["total_ms"] == 0
     plan.profile(0)
     plan.close()
+
+
+# ------------------------------------------------------------------ other patterns, timed plans
+@pytest.mark.parametrize("pattern", [oracle.PATTERN_HALVING_DOUBLING, oracle.PATTERN_SHUFFLE])
+@pytest.mark.parametrize("W,dtype", [(1, oracle.F32), (2, oracle.F32), (4, oracle.F32), (8, oracle.F32), (16, oracle.F32),
+                                     (4, oracle.BF16), (8, oracle.BF16), (16, oracle.BF16)])
+def test_other_patterns_match_the_oracle(pattern, W, dtype):
+    print(f"case: pattern={pattern} W={W} dtype={dtype}", flush=True)
+    cfg = oracle.Config(W, dtype, 8192, oracle.SPLIT_FIXED, 8, 65536, 16, 2, pattern)
+    elems = list(SMALL_ELEMS)
+    grads = make_inputs(cfg, elems, seed=40 + W)
+    ref = oracle_result(cfg, elems, grads)
+    for batch in (cm.BATCH_DIRECT, cm.BATCH_STAGED):
+        plan = lib_plan(cfg, elems, {cm.OPT_BATCH_PATH: batch})
+        dev = Replicas(plan, elems)
+        dev.upload(grads)
+        plan.allreduce()
+        assert_same_bits(dev.download(), ref, f"pattern {pattern} batch path {batch}")
+        plan.close()
+
+
+@pytest.mark.parametrize("W", [3, 5, 33])
+def test_shuffle_with_any_world_size(W):
+    cfg = oracle.Config(W, oracle.F32, 8192, oracle.SPLIT_FIXED, 8, 65536, 16, 2, oracle.PATTERN_SHUFFLE)
+    elems = list(SMALL_ELEMS)
+    grads = make_inputs(cfg, elems, seed=W)
+    ref = oracle_result(cfg, elems, grads)
+    plan = lib_plan(cfg, elems)
+    dev = Replicas(plan, elems)
+    dev.upload(grads)
+    plan.allreduce()
+    assert_same_bits(dev.download(), ref, "shuffle")
+    plan.close()
+
+
+def test_pattern_worked_example_on_the_gpu():
+    n = 52
+    ex = [1.0, 33554432.0, -33554432.0, 5.0]
+    for pattern, want in ((oracle.PATTERN_HALVING_DOUBLING, 1.0), (oracle.PATTERN_SHUFFLE, 1.25)):
+        cfg = oracle.Config(4, oracle.F32, 0, pattern=pattern)
+        plan = lib_plan(cfg, [n])
+        dev = Replicas(plan, [n])
+        dev.upload([[np.full(n, g, dtype=np.float32)] for g in ex])
+        plan.allreduce()
+        got = dev.download()
+        for w in range(4):
+            assert (got[w][0] == np.float32(want)).all()
+        plan.close()
+
+
+def test_timing_aware_plan_runs_bit_exact():
+    elems = list(SMALL_ELEMS)
+    cfg = small_cfg(8, oracle.F32)
+    times = [float(3 * i) for i in range(len(elems))]
+    grads = make_inputs(cfg, elems, seed=9)
+    oplan = oracle.build_plan(cfg, elems, times, 2.0, 0.0005)
+    assert len(oplan.units) != len(oracle.build_plan(cfg, elems).units)      # the timing changes the batches
+    ref = clone(grads)
+    oracle.allreduce(oplan, ref)
+    plan = cm.Plan(cfg.world, elems, dtype=cfg.dtype, batch_threshold_bytes=cfg.batch_threshold_bytes,
+                   split_mode=cfg.split_mode, split_bytes=cfg.split_bytes, ready_time=times, net_a=2.0, net_b=0.0005)
+    assert plan.counts()[0] == len(oplan.units)
+    dev = Replicas(plan, elems)
+    dev.upload(grads)
+    plan.allreduce()
+    assert_same_bits(dev.download(), ref, "timed plan")
+    plan.close()
