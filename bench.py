@@ -36,6 +36,7 @@ def parse_args():
     ap.add_argument("--nontemporal", type=int, default=None)
     ap.add_argument("--unroll", type=int, default=None)
     ap.add_argument("--block", type=int, default=None)
+    ap.add_argument("--pattern", choices=["ring", "hd", "shuffle"], default="ring")
     ap.add_argument("--launch-min-bytes", type=int, default=None)
     ap.add_argument("--device-fill", action="store_true",
                     help="fill the replicas on the device instead of uploading Philox samples")
@@ -86,7 +87,9 @@ def main() -> int:
     streams = args.streams or wl.num_streams
     plan = cm.Plan(wl.world, elems, dtype=wl.dtype, batch_threshold_bytes=wl.batch_threshold_bytes,
                    split_mode=wl.split_mode, split_bytes=wl.split_bytes, max_depth=wl.max_depth,
-                   align_bytes=wl.align_bytes, num_streams=streams)
+                   align_bytes=wl.align_bytes, num_streams=streams,
+                   pattern={"ring": cm.PATTERN_RING, "hd": cm.PATTERN_HALVING_DOUBLING,
+                            "shuffle": cm.PATTERN_SHUFFLE}[args.pattern])
     staged = args.batch_path == "staged"
     if args.launch_mode:
         plan.set_option(cm.OPT_LAUNCH_MODE, {"unit": cm.LAUNCH_PER_UNIT, "stream": cm.LAUNCH_PER_STREAM,
@@ -165,7 +168,8 @@ def main() -> int:
     if not args.no_cpu_baseline:
         import oracle
         ocfg = oracle.Config(wl.world, wl.dtype, wl.batch_threshold_bytes, wl.split_mode, wl.max_depth,
-                             wl.split_bytes, wl.align_bytes, wl.num_streams)
+                             wl.split_bytes, wl.align_bytes, wl.num_streams,
+                             {"ring": 0, "hd": 1, "shuffle": 2}[args.pattern])
         oplan = oracle.build_plan(ocfg, elems)
         if grads is None:
             grads = gradients.replica_set(args.seed, wl.world, elems, bf16=(wl.dtype == cm.BF16), threads=16)
@@ -190,7 +194,7 @@ def main() -> int:
                    "algorithmic_bytes": alg_bytes, "batch_threshold_bytes": wl.batch_threshold_bytes,
                    "split_mode": ["none", "fixed", "adaptive"][wl.split_mode], "split_bytes": wl.split_bytes,
                    "units": plan.counts()[0], "num_streams": streams,
-                   "launch_mode": args.launch_mode or "auto", "batch_path": args.batch_path or "direct"},
+                   "pattern": args.pattern, "launch_mode": args.launch_mode or "auto", "batch_path": args.batch_path or "direct"},
         "roofline": roofline,
         "cpu_baseline": cpu,
     }
