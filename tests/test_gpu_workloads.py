@@ -19,7 +19,8 @@ def cfg_of(wl):
 
 
 @pytest.mark.parametrize("name,seeds", [("mlp", (0, 1, 200414020)), ("resnet50", (0, 1, 200414020)),
-                                        ("inception_v3", (0, 1)), ("vgg16", (0,)), ("transformer", (0,))])
+                                        ("inception_v3", (0, 1)), ("vgg16", (0,)), ("transformer", (0,)),
+                                        ("alexnet_v2", (0,)), ("resnet_v2_152", (0,))])
 def test_workload_bit_exact(name, seeds):
     wl = workload(name)
     cfg = cfg_of(wl)

@@ -11,7 +11,7 @@ import pytest
 import oracle
 import paper_2004_14020_amd as cm
 from paper_2004_14020_amd import binding
-from workloads.shapes import ALL, workload
+from workloads.shapes import ALL, EXTRA, workload
 
 ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
 
@@ -48,7 +48,7 @@ def test_every_declared_symbol_is_exported():
     assert cm.caramel_version() >= 100
 
 
-@pytest.mark.parametrize("name", ALL)
+@pytest.mark.parametrize("name", ALL + EXTRA)
 def test_plan_equals_oracle_on_workloads(name):
     wl = workload(name)
     cfg = oracle.Config(wl.world, wl.dtype, wl.batch_threshold_bytes, wl.split_mode, wl.max_depth,

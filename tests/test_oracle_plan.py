@@ -14,7 +14,7 @@ import pytest
 import oracle
 from oracle import (BF16, F32, KIND_BATCH, KIND_CHUNK, SPLIT_ADAPTIVE, SPLIT_FIXED, SPLIT_NONE,
                     Config, build_plan)
-from workloads.shapes import ALL, workload
+from workloads.shapes import ALL, EXTRA, workload
 
 GOLDEN = os.path.join(os.path.dirname(__file__), "golden")
 
@@ -182,7 +182,7 @@ def test_invariants_random(rounds=500):
         assert again == plan                     # deterministic
 
 
-@pytest.mark.parametrize("name", ALL)
+@pytest.mark.parametrize("name", ALL + EXTRA)
 def test_invariants_workloads(name):
     wl = workload(name)
     cfg = cfg_of(wl)

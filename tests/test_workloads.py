@@ -3,7 +3,7 @@ import numpy as np
 import pytest
 
 from workloads import gradients
-from workloads.shapes import ALL, workload
+from workloads.shapes import ALL, EXTRA, workload
 
 
 def test_tensor_counts_and_sizes():
@@ -22,7 +22,15 @@ def test_vgg16_matches_the_papers_model_table():
     assert wl.algorithmic_bytes() == 8854882816
 
 
-@pytest.mark.parametrize("name", ALL)
+def test_extra_models_match_the_papers_model_table():
+    # section 6, "DNN models": AlexNet-v2 16 parameters / 191.9 MiB, ResNet-v2-152 363 / 229.5 MiB
+    for name, count, mib in (("alexnet_v2", 16, 191.9), ("resnet_v2_152", 363, 229.5)):
+        wl = workload(name)
+        assert len(wl.tensors) == count
+        assert round(wl.total_elems * 4 / 2 ** 20, 1) == mib
+
+
+@pytest.mark.parametrize("name", ALL + EXTRA)
 def test_half_of_the_parameters_are_under_20_kb(name):
     # section 3.3.2 (C): at least 50 % of parameters are smaller than 20 KB in every model
     wl = workload(name)

@@ -134,6 +134,39 @@ def transformer_encoder() -> List[Tensor]:
     return out
 
 
+def alexnet_v2() -> List[Tensor]:
+    """The paper's model table lists 16 parameters, 191.9 MiB (section 6, "DNN models")."""
+    out: List[Tensor] = []
+    layers = [(11, 11, 3, 64), (5, 5, 64, 192), (3, 3, 192, 384), (3, 3, 384, 384), (3, 3, 384, 256),
+              (5, 5, 256, 4096), (1, 1, 4096, 4096), (1, 1, 4096, 1000)]      # fc6-fc8 are convolutions
+    for i, (kh, kw, cin, cout) in enumerate(layers, start=1):
+        out.append((f"l{i}.w", (kh, kw, cin, cout)))
+        out.append((f"l{i}.b", (cout,)))
+    return out
+
+
+def resnet_v2_152() -> List[Tensor]:
+    """Pre-activation ResNet-152 with beta-only batch norms: the paper's table lists 363
+    parameters, 229.5 MiB."""
+    out: List[Tensor] = [("conv1.w", (7, 7, 3, 64)), ("conv1.b", (64,))]
+    cin = 64
+    for stage, (units, p) in enumerate(zip([3, 8, 36, 3], [64, 128, 256, 512]), start=1):
+        for u in range(units):
+            pre = f"b{stage}.u{u}"
+            out.append((f"{pre}.preact.beta", (cin,)))
+            if u == 0:
+                out.append((f"{pre}.shortcut.w", (1, 1, cin, 4 * p)))
+                out.append((f"{pre}.shortcut.b", (4 * p,)))
+            out.append((f"{pre}.conv1.w", (1, 1, cin, p))); out.append((f"{pre}.conv1.bn.beta", (p,)))
+            out.append((f"{pre}.conv2.w", (3, 3, p, p))); out.append((f"{pre}.conv2.bn.beta", (p,)))
+            out.append((f"{pre}.conv3.w", (1, 1, p, 4 * p))); out.append((f"{pre}.conv3.b", (4 * p,)))
+            cin = 4 * p
+    out.append(("postnorm.beta", (2048,)))
+    out.append(("logits.w", (1, 1, 2048, 1000)))
+    out.append(("logits.b", (1000,)))
+    return out
+
+
 # --------------------------------------------------------------------------
 # configurations
 # --------------------------------------------------------------------------
@@ -192,7 +225,13 @@ def workload(name: str) -> Workload:
         return Workload("inception_v3", tuple(inception_v3()), 16, F32, 2 * MB, SPLIT_ADAPTIVE, 8 * MB)
     if name == "transformer":
         return Workload("transformer", tuple(transformer_encoder()), 8, BF16, 4 * MB, SPLIT_FIXED, 16 * MB)
+    # the two remaining models of the paper's table, with the VGG-16 plan parameters
+    if name == "alexnet_v2":
+        return Workload("alexnet_v2", tuple(alexnet_v2()), 8, F32, 1 * MB, SPLIT_FIXED, 4 * MB)
+    if name == "resnet_v2_152":
+        return Workload("resnet_v2_152", tuple(resnet_v2_152()), 8, F32, 1 * MB, SPLIT_FIXED, 4 * MB)
     raise KeyError(name)
 
 
 ALL = ("mlp", "resnet50", "vgg16", "inception_v3", "transformer")
+EXTRA = ("alexnet_v2", "resnet_v2_152")
