@@ -211,7 +211,8 @@ enum {
    * without materialising the fused buffer (same segments, same order, same bits).
    * Default DIRECT. */
   CARAMEL_OPT_BATCH_PATH = 1,
-  /* 16-byte vectors per replica handled by one workgroup tile of the reduce kernel. */
+  /* 16-byte vectors per replica in one workgroup tile of the reduce kernel, for large units
+   * (chunk units of at least CARAMEL_OPT_LARGE_UNIT_BYTES per replica).  Default 1024. */
   CARAMEL_OPT_TILE_VECS = 2,
   /* Upper bound on workgroups per reduce launch (0 = one workgroup per tile). */
   CARAMEL_OPT_MAX_GRID = 3,
@@ -219,7 +220,7 @@ enum {
   CARAMEL_OPT_NONTEMPORAL = 4,
   /* 16-byte vectors each lane keeps in flight per worker: 1, 2 or 4; 0 = chosen from W. */
   CARAMEL_OPT_UNROLL = 5,
-  /* Lanes per workgroup of the reduce kernel: 256, 512 or 1024. */
+  /* Lanes per workgroup of the reduce kernel over large units: 256, 512 or 1024. */
   CARAMEL_OPT_BLOCK = 6,
   /* PER_UNIT launches only: consecutive units of one stream share a launch until it covers at
    * least this many bytes per replica (0 = strictly one launch per unit).  The launch-side
@@ -228,7 +229,14 @@ enum {
   /* AUTO launch mode only: a call whose algorithmic bytes (2 * world * elements * element size)
    * are below this value is not pipelined: it runs as one launch per stage on the caller's
    * stream, with no fork or join.  Default 256 MiB. */
-  CARAMEL_OPT_PIPELINE_MIN_BYTES = 8
+  CARAMEL_OPT_PIPELINE_MIN_BYTES = 8,
+  /* Tile size and workgroup size for all other units (batch units, whose tiles are cut at
+   * member boundaries, and small chunks).  Defaults 256 and 256. */
+  CARAMEL_OPT_SMALL_TILE_VECS = 9,
+  CARAMEL_OPT_SMALL_BLOCK = 10,
+  /* Bytes per replica from which a chunk unit counts as large.  Default 4 MiB.  Large and small
+   * units never share a launch. */
+  CARAMEL_OPT_LARGE_UNIT_BYTES = 11
 };
 enum { CARAMEL_LAUNCH_PER_UNIT = 0, CARAMEL_LAUNCH_PER_STREAM = 1, CARAMEL_LAUNCH_AUTO = 2 };
 enum { CARAMEL_BATCH_STAGED = 0, CARAMEL_BATCH_DIRECT = 1 };

@@ -41,12 +41,12 @@ int fail(int code, const char* fmt, ...) {
 struct Options {
   uint32_t launch_mode = CARAMEL_LAUNCH_AUTO;
   uint32_t batch_path = CARAMEL_BATCH_DIRECT;
-  uint32_t tile_vecs = 1024;
-  uint32_t copy_vecs = 512;
+  TileShape shape;
   uint32_t max_grid = 0;
   uint32_t nontemporal = 1;
   uint32_t unroll = 0;
-  uint32_t block = 1024;
+  uint32_t block = 1024;        // workgroup of launches over large units
+  uint32_t small_block = 256;   // ... over everything else
   uint64_t launch_min_bytes = 4u << 20;
   uint64_t pipeline_min_bytes = uint64_t(256) << 20;
 };
@@ -58,6 +58,7 @@ constexpr unsigned kOrderOnly = hipEventDisableTiming | hipEventDisableSystemFen
 struct LaunchGroup {
   uint32_t stream, first_unit;
   Range reduce, copy;
+  bool large;  // made of large units only: large tiles, large workgroups
 };
 
 struct TimedLaunch {
@@ -166,7 +167,7 @@ struct Timed {
   }
 };
 
-int run_reduce(caramel_plan* p, bool direct, Range r, hipStream_t s) {
+int run_reduce(caramel_plan* p, bool direct, Range r, bool large, hipStream_t s) {
   if (r.count == 0) return CARAMEL_OK;
   ReduceArgs a{};
   a.tiles = direct ? p->d_direct : p->d_staged;
@@ -178,9 +179,10 @@ int run_reduce(caramel_plan* p, bool direct, Range r, hipStream_t s) {
   a.nontemporal = p->opt.nontemporal != 0;
   a.tree = p->host.cfg.pattern == CARAMEL_PATTERN_HALVING_DOUBLING;
   // by default a workgroup takes its tile in one go: vectors per lane = tile / workgroup size
-  a.unroll = p->opt.unroll ? p->opt.unroll : std::max(1u, p->opt.tile_vecs / p->opt.block);
+  a.block = large ? p->opt.block : p->opt.small_block;
+  const uint32_t tile_vecs = large ? p->opt.shape.large_vecs : p->opt.shape.small_vecs;
+  a.unroll = p->opt.unroll ? p->opt.unroll : std::max(1u, tile_vecs / a.block);
   a.max_grid = p->opt.max_grid;
-  a.block = p->opt.block;
   Timed timer(p, CARAMEL_K_REDUCE, s);
   HIP_TRY(launch_ring_reduce(a, s));
   return CARAMEL_OK;
@@ -257,7 +259,7 @@ const std::vector<LaunchGroup>& launch_groups(caramel_plan* p, bool direct) {
     // not pipelined: both plan streams run on the caller's stream, and since the tables hold
     // stream 0's tiles followed by stream 1's, one launch per stage covers everything
     const std::vector<ReduceTile>& all = direct ? tt.direct : tt.staged;
-    out.push_back(LaunchGroup{0, 0, Range{0, uint32_t(all.size())}, Range{0, uint32_t(tt.copy.size())}});
+    out.push_back(LaunchGroup{0, 0, Range{0, uint32_t(all.size())}, Range{0, uint32_t(tt.copy.size())}, false});
     p->groups_stale[direct ? 1 : 0] = false;
     return out;
   }
@@ -267,8 +269,14 @@ const std::vector<LaunchGroup>& launch_groups(caramel_plan* p, bool direct) {
     uint64_t bytes = 0;
     bool open = false;
     for (uint32_t u : tt.stream_units[s]) {
+      const bool large = is_large_unit(p->host, u, p->opt.shape);
+      // tile shape and workgroup size go together, so large and small units never share a launch
+      if (open && g.large != large) {
+        out.push_back(g);
+        open = false;
+      }
       if (!open) {
-        g = LaunchGroup{s, u, Range{unit_tiles[u].begin, 0}, Range{tt.copy_unit[u].begin, 0}};
+        g = LaunchGroup{s, u, Range{unit_tiles[u].begin, 0}, Range{tt.copy_unit[u].begin, 0}, large};
         bytes = 0;
         open = true;
       }
@@ -302,7 +310,7 @@ int pipeline(caramel_plan* p, hipStream_t user, bool with_copies, bool direct) {
   for (const LaunchGroup& g : launch_groups(p, direct)) {
     hipStream_t s = lane[g.stream];
     if (copies) rc = run_copy(p, false, g.copy, s);
-    if (!rc) rc = run_reduce(p, direct, g.reduce, s);
+    if (!rc) rc = run_reduce(p, direct, g.reduce, g.large, s);
     if (!rc && copies) rc = run_copy(p, true, g.copy, s);
     if (rc) break;
   }
@@ -470,7 +478,19 @@ int caramel_plan_set_option(caramel_plan* p, uint32_t option, uint64_t value) {
       return CARAMEL_OK;
     case CARAMEL_OPT_TILE_VECS:
       if (value < 64 || value > (1u << 20)) return fail(CARAMEL_EINVAL, "tile_vecs must be in [64, 2^20]");
-      p->opt.tile_vecs = uint32_t(value);
+      p->opt.shape.large_vecs = uint32_t(value);
+      return CARAMEL_OK;
+    case CARAMEL_OPT_SMALL_TILE_VECS:
+      if (value < 64 || value > (1u << 20)) return fail(CARAMEL_EINVAL, "tile_vecs must be in [64, 2^20]");
+      p->opt.shape.small_vecs = uint32_t(value);
+      return CARAMEL_OK;
+    case CARAMEL_OPT_SMALL_BLOCK:
+      if (value != 256 && value != 512 && value != 1024) return fail(CARAMEL_EINVAL, "block must be 256, 512 or 1024");
+      p->opt.small_block = uint32_t(value);
+      return CARAMEL_OK;
+    case CARAMEL_OPT_LARGE_UNIT_BYTES:
+      p->opt.shape.large_bytes = value;
+      p->groups_stale[0] = p->groups_stale[1] = true;
       return CARAMEL_OK;
     case CARAMEL_OPT_MAX_GRID:
       if (value > 0x7FFFFFFFu) return fail(CARAMEL_EINVAL, "max_grid too large");
@@ -532,7 +552,7 @@ int caramel_bind(caramel_plan* p, void* const* grads, void* fused_ws) {
     if (p->streams[s]) HIP_TRY(hipStreamSynchronize(p->streams[s]));
   release_device(p);
 
-  build_tiles(h, p->opt.tile_vecs, p->opt.copy_vecs, p->tt);
+  build_tiles(h, p->opt.shape, p->tt);
   p->groups_stale[0] = p->groups_stale[1] = true;
   std::vector<uint64_t> rows((n + 1) * W, 0);
   for (uint32_t w = 0; w < W; ++w) {

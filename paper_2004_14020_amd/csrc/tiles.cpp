@@ -20,12 +20,11 @@ void cut_run(std::vector<ReduceTile>& out, uint32_t row, uint32_t first, uint64_
 
 }  // namespace
 
-void build_tiles(const HostPlan& p, uint32_t tile_vecs, uint32_t copy_vecs, TileTables& out) {
+void build_tiles(const HostPlan& p, const TileShape& ts, TileTables& out) {
   out = TileTables{};
   const uint32_t W = p.cfg.world;
   const uint64_t ve = 16 / p.elem_size();  // elements per 16-byte vector
-  const uint64_t tile_elems = uint64_t(tile_vecs) * ve;
-  const uint64_t copy_elems = uint64_t(copy_vecs) * ve;
+  const uint64_t copy_elems = uint64_t(ts.copy_vecs) * ve;
   const uint32_t fused_row = uint32_t(p.tensor_elems.size());
   const size_t nu = p.units.size();
   out.staged_unit.resize(nu);
@@ -42,6 +41,7 @@ void build_tiles(const HostPlan& p, uint32_t tile_vecs, uint32_t copy_vecs, Tile
       out.stream_units[s].push_back(ui);
       const uint64_t* seg = p.segments(ui);
       const caramel_entry* ent = &p.entries[u.first_entry];
+      const uint64_t tile_elems = uint64_t(is_large_unit(p, ui, ts) ? ts.large_vecs : ts.small_vecs) * ve;
       out.staged_unit[ui].begin = uint32_t(out.staged.size());
       out.direct_unit[ui].begin = uint32_t(out.direct.size());
       out.copy_unit[ui].begin = uint32_t(out.copy.size());

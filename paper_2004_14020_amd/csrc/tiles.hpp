@@ -43,7 +43,20 @@ struct TileTables {
   std::vector<uint32_t> stream_units[2];  // unit indices in launch order
 };
 
-// tile_vecs: vectors per reduce tile; copy_vecs: vectors per copy tile.
-void build_tiles(const HostPlan& p, uint32_t tile_vecs, uint32_t copy_vecs, TileTables& out);
+struct TileShape {
+  uint32_t large_vecs = 1024;        // vectors per reduce tile of a large chunk unit
+  uint32_t small_vecs = 256;         // ... of every other unit
+  uint64_t large_bytes = 4u << 20;   // a chunk unit of at least this many bytes per replica is "large"
+  uint32_t copy_vecs = 512;          // vectors per copy tile
+};
+
+// A unit whose tiles have the large shape: long uniform runs, worth 1024-lane workgroups.
+// Batch units are cut at member boundaries into many short runs and get the small shape.
+inline bool is_large_unit(const HostPlan& p, uint32_t unit, const TileShape& ts) {
+  const caramel_unit& u = p.units[unit];
+  return u.kind == CARAMEL_KIND_CHUNK && u.elems * p.elem_size() >= ts.large_bytes;
+}
+
+void build_tiles(const HostPlan& p, const TileShape& ts, TileTables& out);
 
 }  // namespace caramel

@@ -26,14 +26,19 @@ static int fails = 0;
   } while (0)
 
 static void check_case(const caramel_config& cfg, const std::vector<uint64_t>& elems, uint32_t tile_vecs,
-                       uint32_t copy_vecs) {
+                       uint32_t small_vecs, uint64_t large_bytes, uint32_t copy_vecs) {
   HostPlan p;
   std::string why;
   const int rc = build_host_plan(cfg, elems.data(), uint32_t(elems.size()), nullptr, 0.0, 0.0, p, why);
   CHECK(rc == CARAMEL_OK);
   if (rc != CARAMEL_OK) return;
   TileTables tt;
-  build_tiles(p, tile_vecs, copy_vecs, tt);
+  TileShape shape;
+  shape.large_vecs = tile_vecs;
+  shape.small_vecs = small_vecs;
+  shape.large_bytes = large_bytes;
+  shape.copy_vecs = copy_vecs;
+  build_tiles(p, shape, tt);
   const uint64_t es = p.elem_size(), ve = 16 / es, W = cfg.world;
   const uint32_t fused_row = uint32_t(elems.size());
   auto row_elems = [&](uint32_t row) { return row == fused_row ? p.fused_elems : elems[row]; };
@@ -52,7 +57,7 @@ static void check_case(const caramel_config& cfg, const std::vector<uint64_t>& e
       total_tiles += r.count;
       for (uint32_t i = r.begin; i < r.begin + r.count; ++i) {
         const ReduceTile& t = tiles[i];
-        CHECK(t.n_elems > 0 && t.n_elems <= uint64_t(tile_vecs) * ve);
+        CHECK(t.n_elems > 0 && t.n_elems <= uint64_t(is_large_unit(p, u, shape) ? tile_vecs : small_vecs) * ve);
         CHECK(t.first < W);
         CHECK(t.row <= fused_row);
         const uint64_t e0 = uint64_t(t.vec_off) * ve, e1 = e0 + t.n_elems;
@@ -158,7 +163,8 @@ int main() {
     if (cfg.pattern == CARAMEL_PATTERN_HALVING_DOUBLING) cfg.world = uint32_t(pick({1, 2, 4, 8, 16}));
     std::vector<uint64_t> elems(1 + rng() % 14);
     for (uint64_t& e : elems) e = pick({1, 2, 3, 5, 8, 17, 64, 100, 255, 256, 257, 1000, 4096, 5000, 70000});
-    check_case(cfg, elems, uint32_t(pick({64, 256, 1024, 4096})), uint32_t(pick({64, 512})));
+    check_case(cfg, elems, uint32_t(pick({64, 256, 1024, 4096})), uint32_t(pick({64, 256, 1024})),
+               pick({0, 1024, 65536, 1u << 22}), uint32_t(pick({64, 512})));
   }
   // rejected configurations must not crash
   HostPlan p;
