@@ -169,7 +169,9 @@ int caramel_plan_serialize(const caramel_plan* plan, void* buf, size_t* len);
 /* Attach memory to a plan.
  *   grads     host array of world * n_tensors DEVICE pointers; grads[w * n_tensors + t] is
  *             worker w's tensor t (tensor_elems[t] elements of the plan's dtype), aligned to
- *             align_bytes.  Replicas must not overlap.
+ *             align_bytes.  Replicas must not overlap.  (Any such pointers are correct; large
+ *             tensors stream fastest when they start on 64 KiB boundaries, because the reduce
+ *             kernel's large tiles then coincide with aligned 64 KiB blocks of memory.)
  *   fused_ws  DEVICE workspace of world * fused_elems elements (replica w's fused buffer starts
  *             at element w * fused_elems); may be NULL when fused_elems == 0, or when only
  *             caramel_allreduce in its default (direct) mode is going to be used.
@@ -212,7 +214,7 @@ enum {
    * Default DIRECT. */
   CARAMEL_OPT_BATCH_PATH = 1,
   /* 16-byte vectors per replica in one workgroup tile of the reduce kernel, for large units
-   * (chunk units of at least CARAMEL_OPT_LARGE_UNIT_BYTES per replica).  Default 1024. */
+   * (chunk units of at least CARAMEL_OPT_LARGE_UNIT_BYTES per replica).  Default 4096. */
   CARAMEL_OPT_TILE_VECS = 2,
   /* Upper bound on workgroups per reduce launch (0 = one workgroup per tile). */
   CARAMEL_OPT_MAX_GRID = 3,
@@ -222,9 +224,11 @@ enum {
   CARAMEL_OPT_UNROLL = 5,
   /* Lanes per workgroup of the reduce kernel over large units: 256, 512 or 1024. */
   CARAMEL_OPT_BLOCK = 6,
-  /* PER_UNIT launches only: consecutive units of one stream share a launch until it covers at
-   * least this many bytes per replica (0 = strictly one launch per unit).  The launch-side
-   * counterpart of the batching threshold: it amortises launch overhead over small units. */
+  /* PER_UNIT launches only: consecutive small units of one stream share a launch until it
+   * covers at least this many bytes per replica (0 = strictly one launch per unit).  The
+   * launch-side counterpart of the batching threshold: it amortises launch overhead over small
+   * units.  Default 4 MiB.  A stream's launches over large units and over small units are
+   * independent sequences; the order in which they are issued does not affect results. */
   CARAMEL_OPT_LAUNCH_MIN_BYTES = 7,
   /* AUTO launch mode only: a call whose algorithmic bytes (2 * world * elements * element size)
    * are below this value is not pipelined: it runs as one launch per stage on the caller's
@@ -236,7 +240,15 @@ enum {
   CARAMEL_OPT_SMALL_BLOCK = 10,
   /* Bytes per replica from which a chunk unit counts as large.  Default 4 MiB.  Large and small
    * units never share a launch. */
-  CARAMEL_OPT_LARGE_UNIT_BYTES = 11
+  CARAMEL_OPT_LARGE_UNIT_BYTES = 11,
+  /* Large units only: 2 or 4 (default) selects the stream-major kernel, which walks the chain
+   * of workers one replica at a time with that many vectors per lane (long contiguous runs per
+   * replica; meant for tiles of block * value vectors); 0 fetches all workers' values at once.
+   * The halving-doubling pattern always uses the latter. */
+  CARAMEL_OPT_STREAM_MAJOR = 12,
+  /* PER_UNIT launches only: like CARAMEL_OPT_LAUNCH_MIN_BYTES, for launches over large units.
+   * Default 64 MiB (the stream-major kernel wants long launches). */
+  CARAMEL_OPT_LARGE_LAUNCH_MIN_BYTES = 13
 };
 enum { CARAMEL_LAUNCH_PER_UNIT = 0, CARAMEL_LAUNCH_PER_STREAM = 1, CARAMEL_LAUNCH_AUTO = 2 };
 enum { CARAMEL_BATCH_STAGED = 0, CARAMEL_BATCH_DIRECT = 1 };

@@ -47,7 +47,10 @@ struct Options {
   uint32_t unroll = 0;
   uint32_t block = 1024;        // workgroup of launches over large units
   uint32_t small_block = 256;   // ... over everything else
-  uint64_t launch_min_bytes = 4u << 20;
+  uint32_t lane_by_class = 0;   // pipeline: large units on the caller's stream, small ones on the internal one
+  uint32_t stream_major = 4;    // vectors per lane of the stream-major kernel for large units (0 = off)
+  uint64_t launch_min_bytes = 4u << 20;         // small units share a launch up to this size
+  uint64_t large_launch_min_bytes = 64u << 20;  // large units likewise
   uint64_t pipeline_min_bytes = uint64_t(256) << 20;
 };
 
@@ -182,6 +185,7 @@ int run_reduce(caramel_plan* p, bool direct, Range r, bool large, hipStream_t s)
   a.block = large ? p->opt.block : p->opt.small_block;
   const uint32_t tile_vecs = large ? p->opt.shape.large_vecs : p->opt.shape.small_vecs;
   a.unroll = p->opt.unroll ? p->opt.unroll : std::max(1u, tile_vecs / a.block);
+  a.stream_major = large ? p->opt.stream_major : 0;
   a.max_grid = p->opt.max_grid;
   Timed timer(p, CARAMEL_K_REDUCE, s);
   HIP_TRY(launch_ring_reduce(a, s));
@@ -232,10 +236,10 @@ int join_streams(caramel_plan* p, hipStream_t user, bool pipelined) {
   return CARAMEL_OK;
 }
 
-// Consecutive units of one stream are launched together until the launch covers at least
-// `launch_min_bytes` per replica (PER_UNIT), or all together (PER_STREAM).  Their tiles are
-// adjacent in the tables, so a group is one tile range.  Groups are issued in the order of their
-// first unit, which alternates between the streams.
+// A launch covers consecutive units of one class (large or small) and one stream; their tiles
+// are adjacent in the tables, so a launch is one tile range.  PER_UNIT: units are added until the
+// launch covers at least the class's minimum bytes per replica.  PER_STREAM: one launch per
+// class and stream.  The order in which a stream's launches are issued does not affect results.
 // AUTO: the two-stream pipeline pays a fixed price for its fork and join (tens of microseconds
 // of cross-stream signalling), so it is used only when a call moves enough bytes to win that
 // back; smaller calls go out as one launch per stream on the caller's stream.
@@ -254,43 +258,42 @@ const std::vector<LaunchGroup>& launch_groups(caramel_plan* p, bool direct) {
   const TileTables& tt = p->tt;
   const std::vector<Range>& unit_tiles = direct ? tt.direct_unit : tt.staged_unit;
   uint32_t mode = p->opt.launch_mode;
-  if (mode == CARAMEL_LAUNCH_AUTO) mode = use_pipeline(p) ? CARAMEL_LAUNCH_PER_UNIT : CARAMEL_LAUNCH_PER_STREAM;
-  if (!use_pipeline(p) && p->host.cfg.num_streams == 2) {
-    // not pipelined: both plan streams run on the caller's stream, and since the tables hold
-    // stream 0's tiles followed by stream 1's, one launch per stage covers everything
-    const std::vector<ReduceTile>& all = direct ? tt.direct : tt.staged;
-    out.push_back(LaunchGroup{0, 0, Range{0, uint32_t(all.size())}, Range{0, uint32_t(tt.copy.size())}, false});
-    p->groups_stale[direct ? 1 : 0] = false;
-    return out;
-  }
+  const bool pipelined = use_pipeline(p);
+  if (mode == CARAMEL_LAUNCH_AUTO) mode = pipelined ? CARAMEL_LAUNCH_PER_UNIT : CARAMEL_LAUNCH_PER_STREAM;
   const uint64_t es = p->host.elem_size();
-  for (uint32_t s = 0; s < p->host.cfg.num_streams; ++s) {
-    LaunchGroup g{};
-    uint64_t bytes = 0;
-    bool open = false;
-    for (uint32_t u : tt.stream_units[s]) {
-      const bool large = is_large_unit(p->host, u, p->opt.shape);
-      // tile shape and workgroup size go together, so large and small units never share a launch
-      if (open && g.large != large) {
-        out.push_back(g);
-        open = false;
+  // Without the pipeline both plan streams run on the caller's stream: treat them as one.
+  const bool by_class = pipelined && p->opt.lane_by_class;
+  const uint32_t lanes = (pipelined && !by_class) ? p->host.cfg.num_streams : 1;
+  for (int cls = 0; cls < 2; ++cls) {
+    const uint64_t min_bytes = cls == kLarge ? p->opt.large_launch_min_bytes : p->opt.launch_min_bytes;
+    for (uint32_t lane = 0; lane < lanes; ++lane) {
+      LaunchGroup g{};
+      uint64_t bytes = 0;
+      bool open = false;
+      for (uint32_t s = 0; s < p->host.cfg.num_streams; ++s) {
+        if (pipelined && !by_class && s != lane) continue;
+        for (uint32_t u : tt.order[cls][s]) {
+          if (!open) {
+            const uint32_t on = by_class ? uint32_t(cls) : lane;
+            g = LaunchGroup{on, u, Range{unit_tiles[u].begin, 0}, Range{tt.copy_unit[u].begin, 0}, cls == kLarge};
+            bytes = 0;
+            open = true;
+          }
+          g.reduce.count += unit_tiles[u].count;
+          g.copy.count += tt.copy_unit[u].count;
+          bytes += p->host.units[u].elems * es;
+          if (mode == CARAMEL_LAUNCH_PER_UNIT && bytes >= min_bytes) {
+            out.push_back(g);
+            open = false;
+          }
+        }
       }
-      if (!open) {
-        g = LaunchGroup{s, u, Range{unit_tiles[u].begin, 0}, Range{tt.copy_unit[u].begin, 0}, large};
-        bytes = 0;
-        open = true;
-      }
-      g.reduce.count += unit_tiles[u].count;
-      g.copy.count += tt.copy_unit[u].count;
-      bytes += p->host.units[u].elems * es;
-      if (mode == CARAMEL_LAUNCH_PER_UNIT && bytes >= p->opt.launch_min_bytes) {
-        out.push_back(g);
-        open = false;
-      }
+      if (open) out.push_back(g);
     }
-    if (open) out.push_back(g);
   }
-  std::sort(out.begin(), out.end(), [](const LaunchGroup& a, const LaunchGroup& b) { return a.first_unit < b.first_unit; });
+  // issue in the order of the first unit, which alternates between the streams
+  std::stable_sort(out.begin(), out.end(),
+                   [](const LaunchGroup& a, const LaunchGroup& b) { return a.first_unit < b.first_unit; });
   p->groups_stale[direct ? 1 : 0] = false;
   return out;
 }
@@ -487,6 +490,18 @@ int caramel_plan_set_option(caramel_plan* p, uint32_t option, uint64_t value) {
     case CARAMEL_OPT_SMALL_BLOCK:
       if (value != 256 && value != 512 && value != 1024) return fail(CARAMEL_EINVAL, "block must be 256, 512 or 1024");
       p->opt.small_block = uint32_t(value);
+      return CARAMEL_OK;
+    case 14:  // experimental: lane by class
+      p->opt.lane_by_class = value ? 1 : 0;
+      p->groups_stale[0] = p->groups_stale[1] = true;
+      return CARAMEL_OK;
+    case CARAMEL_OPT_LARGE_LAUNCH_MIN_BYTES:
+      p->opt.large_launch_min_bytes = value;
+      p->groups_stale[0] = p->groups_stale[1] = true;
+      return CARAMEL_OK;
+    case CARAMEL_OPT_STREAM_MAJOR:
+      if (value != 0 && value != 2 && value != 4) return fail(CARAMEL_EINVAL, "stream_major must be 0, 2 or 4");
+      p->opt.stream_major = uint32_t(value);
       return CARAMEL_OK;
     case CARAMEL_OPT_LARGE_UNIT_BYTES:
       p->opt.shape.large_bytes = value;

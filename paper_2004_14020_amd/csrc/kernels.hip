@@ -199,6 +199,87 @@ k_ring_reduce(const ReduceTile* __restrict__ tiles, const uint64_t* __restrict__
   }
 }
 
+// Stream-major variant for large tiles (chain orders only).  A lane handles U vectors, but
+// instead of fetching all W workers' values at once it walks the chain one worker at a time,
+// with the next worker's U loads in flight while the current ones are added.  A 1024-lane
+// workgroup thus requests 1024*U*16 contiguous bytes of one replica before it moves on to the
+// next replica, which the memory system serves better than many short interleaved runs.
+template <int W, int U, bool BF16, bool NT>
+__global__ void __launch_bounds__(kMaxBlock)
+k_ring_reduce_sm(const ReduceTile* __restrict__ tiles, const uint64_t* __restrict__ rows, uint32_t begin,
+                 uint32_t count, float inv_w) {
+  constexpr uint32_t VE = BF16 ? 8 : 4;
+  for (uint32_t ti = blockIdx.x; ti < count; ti += gridDim.x) {
+    const ReduceTile tl = tiles[begin + ti];
+    gvec_ptr p[W];
+#pragma unroll
+    for (int k = 0; k < W; ++k) {
+      uint32_t w = tl.first + k;
+      if (w >= uint32_t(W)) w -= W;
+      p[k] = reinterpret_cast<gvec_ptr>(rows[size_t(tl.row) * W + w]) + tl.vec_off;
+    }
+    const uint32_t nvec = tl.n_elems / VE;
+    const uint32_t B = blockDim.x;
+    uint32_t v = threadIdx.x;
+    for (; v + (U - 1) * B < nvec; v += U * B) {
+      u32x4 cur[U], nxt[U];
+      Chain<BF16> acc[U];
+#pragma unroll
+      for (int u = 0; u < U; ++u) cur[u] = ld<NT>(at(p[0], (v + u * B) * 16u));
+#pragma unroll
+      for (int k = 1; k < W; ++k) {
+#pragma unroll
+        for (int u = 0; u < U; ++u) nxt[u] = ld<NT>(at(p[k], (v + u * B) * 16u));
+        __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+          if (k == 1) acc[u].start(cur[u]);
+          else acc[u].add(cur[u]);
+          cur[u] = nxt[u];
+        }
+        __builtin_amdgcn_sched_barrier(0);
+      }
+      u32x4 y[U];
+#pragma unroll
+      for (int u = 0; u < U; ++u) {
+        acc[u].add(cur[u]);
+        y[u] = acc[u].finish(inv_w);
+      }
+#pragma unroll
+      for (int k = 0; k < W; ++k)
+#pragma unroll
+        for (int u = 0; u < U; ++u) st<NT>(at(p[k], (v + u * B) * 16u), y[u]);
+    }
+    for (; v < nvec; v += B) {
+      u32x4 x[W];
+#pragma unroll
+      for (int k = 0; k < W; ++k) x[k] = ld<NT>(at(p[k], v * 16u));
+      __builtin_amdgcn_sched_barrier(0);
+      const u32x4 y = combine<W, BF16, false>(x, inv_w);
+#pragma unroll
+      for (int k = 0; k < W; ++k) st<NT>(at(p[k], v * 16u), y);
+    }
+    const uint32_t rem = tl.n_elems - nvec * VE;
+    if (threadIdx.x < rem) {
+      const uint32_t e = nvec * VE + threadIdx.x;
+      float val[W];
+      if constexpr (BF16) {
+#pragma unroll
+        for (int k = 0; k < W; ++k) val[k] = widen(reinterpret_cast<gu16_ptr>(p[k])[e]);
+        const uint16_t y = uint16_t(bf16_rne(combine_scalar<W, false>(val, inv_w)));
+#pragma unroll
+        for (int k = 0; k < W; ++k) reinterpret_cast<gu16_ptr>(p[k])[e] = y;
+      } else {
+#pragma unroll
+        for (int k = 0; k < W; ++k) val[k] = reinterpret_cast<gf32_ptr>(p[k])[e];
+        const float y = combine_scalar<W, false>(val, inv_w);
+#pragma unroll
+        for (int k = 0; k < W; ++k) reinterpret_cast<gf32_ptr>(p[k])[e] = y;
+      }
+    }
+  }
+}
+
 // Any W: pointers are fetched as the chain advances.
 template <bool BF16, bool NT>
 __global__ void __launch_bounds__(kMaxBlock)
@@ -294,8 +375,25 @@ hipError_t launch_w(const ReduceArgs& a, dim3 grid, float inv_w, hipStream_t s) 
   return hipGetLastError();
 }
 
+template <int W, int U>
+hipError_t launch_sm(const ReduceArgs& a, dim3 grid, float inv_w, hipStream_t s) {
+#define CARAMEL_SM(BF, NT) \
+  hipLaunchKernelGGL((k_ring_reduce_sm<W, U, BF, NT>), grid, dim3(a.block), 0, s, a.tiles, a.rows, a.begin, a.count, inv_w)
+  if (a.bf16) {
+    if (a.nontemporal) CARAMEL_SM(true, true); else CARAMEL_SM(true, false);
+  } else {
+    if (a.nontemporal) CARAMEL_SM(false, true); else CARAMEL_SM(false, false);
+  }
+#undef CARAMEL_SM
+  return hipGetLastError();
+}
+
 template <int W>
 hipError_t launch_u(const ReduceArgs& a, dim3 grid, float inv_w, hipStream_t s) {
+  if (a.stream_major && !a.tree) {
+    if (a.stream_major >= 4) return launch_sm<W, 4>(a, grid, inv_w, s);
+    return launch_sm<W, 2>(a, grid, inv_w, s);
+  }
   // W * U vectors per lane must fit the register budget of a 1024-lane workgroup
   constexpr uint32_t kMaxU = W <= 4 ? 4 : (W <= 8 ? 2 : 1);
   uint32_t u = a.unroll ? a.unroll : kMaxU;

@@ -18,6 +18,8 @@ struct ReduceArgs {
   uint32_t unroll;    // vectors in flight per lane and worker: 1, 2 or 4 (0 = choose from W)
   uint32_t max_grid;  // 0 = one workgroup per tile
   uint32_t block;     // lanes per workgroup: 256, 512 or 1024
+  uint32_t stream_major;  // 0: fetch all workers at once; 2 or 4: walk the chain worker by worker,
+                          // that many vectors per lane (chain orders only)
 };
 
 struct CopyArgs {

@@ -30,65 +30,59 @@ void build_tiles(const HostPlan& p, const TileShape& ts, TileTables& out) {
   out.staged_unit.resize(nu);
   out.direct_unit.resize(nu);
   out.copy_unit.resize(nu);
+  for (uint32_t ui = 0; ui < nu; ++ui)
+    out.order[is_large_unit(p, ui, ts) ? kLarge : kSmall][p.units[ui].stream].push_back(ui);
 
-  for (uint32_t s = 0; s < p.cfg.num_streams; ++s) {
-    out.staged_stream[s].begin = uint32_t(out.staged.size());
-    out.direct_stream[s].begin = uint32_t(out.direct.size());
-    out.copy_stream[s].begin = uint32_t(out.copy.size());
-    for (uint32_t ui = 0; ui < nu; ++ui) {
-      const caramel_unit& u = p.units[ui];
-      if (u.stream != s) continue;
-      out.stream_units[s].push_back(ui);
-      const uint64_t* seg = p.segments(ui);
-      const caramel_entry* ent = &p.entries[u.first_entry];
-      const uint64_t tile_elems = uint64_t(is_large_unit(p, ui, ts) ? ts.large_vecs : ts.small_vecs) * ve;
-      out.staged_unit[ui].begin = uint32_t(out.staged.size());
-      out.direct_unit[ui].begin = uint32_t(out.direct.size());
-      out.copy_unit[ui].begin = uint32_t(out.copy.size());
+  for (int cls = 0; cls < 2; ++cls)
+    for (uint32_t s = 0; s < p.cfg.num_streams; ++s)
+      for (uint32_t ui : out.order[cls][s]) {
+        const caramel_unit& u = p.units[ui];
+        const uint64_t* seg = p.segments(ui);
+        const caramel_entry* ent = &p.entries[u.first_entry];
+        const uint64_t tile_elems = uint64_t(cls == kLarge ? ts.large_vecs : ts.small_vecs) * ve;
+        out.staged_unit[ui].begin = uint32_t(out.staged.size());
+        out.direct_unit[ui].begin = uint32_t(out.direct.size());
+        out.copy_unit[ui].begin = uint32_t(out.copy.size());
 
-      for (uint32_t c = 0; c < W; ++c) {
-        const uint64_t a = seg[c], b = seg[c + 1];
-        if (a == b) continue;
-        // ring: the chain of segment c starts at worker c+1; the other patterns add in an
-        // order that does not depend on the segment and read the workers from 0
-        const uint32_t first = p.cfg.pattern == CARAMEL_PATTERN_RING ? (c + 1) % W : 0;
-        if (u.kind == CARAMEL_KIND_CHUNK) {
-          cut_run(out.staged, ent[0].tensor, first, ent[0].tensor_off + a, b - a, ve, tile_elems);
-          cut_run(out.direct, ent[0].tensor, first, ent[0].tensor_off + a, b - a, ve, tile_elems);
-          continue;
-        }
-        cut_run(out.staged, fused_row, first, u.fused_off + a, b - a, ve, tile_elems);
-        for (uint32_t k = 0; k < u.n_entries; ++k) {
-          const caramel_entry& e = ent[k];
-          const uint64_t lo = std::max(a, e.unit_off), hi = std::min(b, e.unit_off + e.elems);
-          if (lo >= hi) continue;
-          cut_run(out.direct, e.tensor, first, e.tensor_off + (lo - e.unit_off), hi - lo, ve, tile_elems);
-        }
-      }
-
-      if (u.kind == CARAMEL_KIND_BATCH) {
-        for (uint32_t k = 0; k < u.n_entries; ++k) {
-          const caramel_entry& e = ent[k];
-          const uint64_t next = (k + 1 < u.n_entries) ? ent[k + 1].unit_off : u.elems;
-          for (uint64_t at = 0; at < e.elems; at += copy_elems) {
-            CopyTile t{};
-            t.row = e.tensor;
-            t.t_vec_off = uint32_t((e.tensor_off + at) / ve);
-            t.f_vec_off = uint32_t((u.fused_off + e.unit_off + at) / ve);
-            t.n_elems = uint32_t(std::min(copy_elems, e.elems - at));
-            t.n_zero = (at + copy_elems >= e.elems) ? uint32_t(next - (e.unit_off + e.elems)) : 0;
-            out.copy.push_back(t);
+        for (uint32_t c = 0; c < W; ++c) {
+          const uint64_t a = seg[c], b = seg[c + 1];
+          if (a == b) continue;
+          // ring: the chain of segment c starts at worker c+1; the other patterns add in an
+          // order that does not depend on the segment and read the workers from 0
+          const uint32_t first = p.cfg.pattern == CARAMEL_PATTERN_RING ? (c + 1) % W : 0;
+          if (u.kind == CARAMEL_KIND_CHUNK) {
+            cut_run(out.staged, ent[0].tensor, first, ent[0].tensor_off + a, b - a, ve, tile_elems);
+            cut_run(out.direct, ent[0].tensor, first, ent[0].tensor_off + a, b - a, ve, tile_elems);
+            continue;
+          }
+          cut_run(out.staged, fused_row, first, u.fused_off + a, b - a, ve, tile_elems);
+          for (uint32_t k = 0; k < u.n_entries; ++k) {
+            const caramel_entry& e = ent[k];
+            const uint64_t lo = std::max(a, e.unit_off), hi = std::min(b, e.unit_off + e.elems);
+            if (lo >= hi) continue;
+            cut_run(out.direct, e.tensor, first, e.tensor_off + (lo - e.unit_off), hi - lo, ve, tile_elems);
           }
         }
+
+        if (u.kind == CARAMEL_KIND_BATCH) {
+          for (uint32_t k = 0; k < u.n_entries; ++k) {
+            const caramel_entry& e = ent[k];
+            const uint64_t next = (k + 1 < u.n_entries) ? ent[k + 1].unit_off : u.elems;
+            for (uint64_t at = 0; at < e.elems; at += copy_elems) {
+              CopyTile t{};
+              t.row = e.tensor;
+              t.t_vec_off = uint32_t((e.tensor_off + at) / ve);
+              t.f_vec_off = uint32_t((u.fused_off + e.unit_off + at) / ve);
+              t.n_elems = uint32_t(std::min(copy_elems, e.elems - at));
+              t.n_zero = (at + copy_elems >= e.elems) ? uint32_t(next - (e.unit_off + e.elems)) : 0;
+              out.copy.push_back(t);
+            }
+          }
+        }
+        out.staged_unit[ui].count = uint32_t(out.staged.size()) - out.staged_unit[ui].begin;
+        out.direct_unit[ui].count = uint32_t(out.direct.size()) - out.direct_unit[ui].begin;
+        out.copy_unit[ui].count = uint32_t(out.copy.size()) - out.copy_unit[ui].begin;
       }
-      out.staged_unit[ui].count = uint32_t(out.staged.size()) - out.staged_unit[ui].begin;
-      out.direct_unit[ui].count = uint32_t(out.direct.size()) - out.direct_unit[ui].begin;
-      out.copy_unit[ui].count = uint32_t(out.copy.size()) - out.copy_unit[ui].begin;
-    }
-    out.staged_stream[s].count = uint32_t(out.staged.size()) - out.staged_stream[s].begin;
-    out.direct_stream[s].count = uint32_t(out.direct.size()) - out.direct_stream[s].begin;
-    out.copy_stream[s].count = uint32_t(out.copy.size()) - out.copy_stream[s].begin;
-  }
 }
 
 }  // namespace caramel

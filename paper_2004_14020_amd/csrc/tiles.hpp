@@ -33,18 +33,8 @@ struct Range {
   uint32_t begin = 0, count = 0;
 };
 
-struct TileTables {
-  std::vector<ReduceTile> staged;  // batch units on the fused row, chunk units on tensor rows
-  std::vector<ReduceTile> direct;  // batch units addressed through their member tensors
-  std::vector<CopyTile> copy;
-  // tile ranges per unit and per internal stream (tables are ordered by stream, then unit)
-  std::vector<Range> staged_unit, direct_unit, copy_unit;
-  Range staged_stream[2], direct_stream[2], copy_stream[2];
-  std::vector<uint32_t> stream_units[2];  // unit indices in launch order
-};
-
 struct TileShape {
-  uint32_t large_vecs = 1024;        // vectors per reduce tile of a large chunk unit
+  uint32_t large_vecs = 4096;        // vectors per reduce tile of a large chunk unit
   uint32_t small_vecs = 256;         // ... of every other unit
   uint64_t large_bytes = 4u << 20;   // a chunk unit of at least this many bytes per replica is "large"
   uint32_t copy_vecs = 512;          // vectors per copy tile
@@ -56,6 +46,20 @@ inline bool is_large_unit(const HostPlan& p, uint32_t unit, const TileShape& ts)
   const caramel_unit& u = p.units[unit];
   return u.kind == CARAMEL_KIND_CHUNK && u.elems * p.elem_size() >= ts.large_bytes;
 }
+
+enum { kLarge = 0, kSmall = 1 };
+
+struct TileTables {
+  std::vector<ReduceTile> staged;  // batch units on the fused row, chunk units on tensor rows
+  std::vector<ReduceTile> direct;  // batch units addressed through their member tensors
+  std::vector<CopyTile> copy;
+  // Units appear in the tables class by class, stream by stream: the large units of stream 0,
+  // of stream 1, then the small units of stream 0, of stream 1 -- each in unit order.  So the
+  // tiles of consecutive units of one class and stream are adjacent, and so are all tiles of
+  // one class.
+  std::vector<uint32_t> order[2][2];  // [class][stream] -> unit indices
+  std::vector<Range> staged_unit, direct_unit, copy_unit;  // tile range of every unit
+};
 
 void build_tiles(const HostPlan& p, const TileShape& ts, TileTables& out);
 

@@ -20,10 +20,13 @@ def _round_up(x: int, a: int) -> int:
 class Replicas:
     """W replicas of a gradient set in device memory, one contiguous arena per replica.
 
-    Tensor t of every replica starts `slot` bytes into its arena, slots being rounded up
-    to `slot_align` bytes, like the flat gradient buffer of a training framework."""
+    Tensor t of every replica starts at the same offset in its arena, like the flat gradient
+    buffer of a training framework.  Tensors of at least `large_bytes` start on `large_align`
+    boundaries (64 KiB: the reduce kernel's large tiles then coincide with aligned 64 KiB
+    blocks of memory, which it streams measurably faster); the others on `slot_align`."""
 
     def __init__(self, plan: Plan, elems: Sequence[int], device: str = "cuda:0", slot_align: int = 256,
+                 large_align: int = 65536, large_bytes: int = 1 << 20,
                  with_workspace: bool = True):
         self.plan = plan
         self.world = plan.cfg.world
@@ -34,8 +37,9 @@ class Replicas:
         self.device = torch.device(device)
         offs, at = [], 0
         for n in self.elems:
+            at = _round_up(at, large_align if n * self.es >= large_bytes else slot_align)
             offs.append(at)
-            at = _round_up(at + n * self.es, slot_align)
+            at += n * self.es
         self.offsets = offs
         self.arena_bytes = max(at, slot_align)
         self.arenas = [torch.empty(self.arena_bytes, dtype=torch.uint8, device=self.device)

@@ -117,13 +117,17 @@ static void check_case(const caramel_config& cfg, const std::vector<uint64_t>& e
       const std::vector<uint8_t>& s = seen[fused_row];
       CHECK(s.size() == p.fused_elems && std::all_of(s.begin(), s.end(), [](uint8_t b) { return b == 1; }));
     }
-    // stream ranges partition the table in order
+    // the unit ranges follow one another in the documented order: large units of stream 0,
+    // of stream 1, small units of stream 0, of stream 1
     uint32_t at = 0;
-    const Range* sr = table ? tt.direct_stream : tt.staged_stream;
-    for (uint32_t s = 0; s < cfg.num_streams; ++s) {
-      CHECK(sr[s].begin == at);
-      at += sr[s].count;
-    }
+    for (int cls = 0; cls < 2; ++cls)
+      for (uint32_t s = 0; s < cfg.num_streams; ++s)
+        for (uint32_t u : tt.order[cls][s]) {
+          CHECK(p.units[u].stream == s);
+          CHECK(is_large_unit(p, u, shape) == (cls == kLarge));
+          CHECK(per_unit[u].begin == at);
+          at += per_unit[u].count;
+        }
     CHECK(at == tiles.size());
   }
 
