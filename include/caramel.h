@@ -214,7 +214,8 @@ enum {
    * Default DIRECT. */
   CARAMEL_OPT_BATCH_PATH = 1,
   /* 16-byte vectors per replica in one workgroup tile of the reduce kernel, for large units
-   * (chunk units of at least CARAMEL_OPT_LARGE_UNIT_BYTES per replica).  Default 4096. */
+   * (chunk units of at least CARAMEL_OPT_LARGE_UNIT_BYTES per replica) of a stream whose large
+   * units total at least CARAMEL_OPT_LONG_LAUNCH_BYTES.  Default 4096. */
   CARAMEL_OPT_TILE_VECS = 2,
   /* Upper bound on workgroups per reduce launch (0 = one workgroup per tile). */
   CARAMEL_OPT_MAX_GRID = 3,
@@ -248,7 +249,14 @@ enum {
   CARAMEL_OPT_STREAM_MAJOR = 12,
   /* PER_UNIT launches only: like CARAMEL_OPT_LAUNCH_MIN_BYTES, for launches over large units.
    * Default 64 MiB (the stream-major kernel wants long launches). */
-  CARAMEL_OPT_LARGE_LAUNCH_MIN_BYTES = 13
+  CARAMEL_OPT_LARGE_LAUNCH_MIN_BYTES = 13,
+  CARAMEL_OPT_RESERVED_14 = 14,
+  /* Large units of a stream get the long-launch treatment (large tiles, stream-major kernel,
+   * launches of CARAMEL_OPT_LARGE_LAUNCH_MIN_BYTES) only if they total at least this many bytes
+   * per replica; default 64 MiB.  Otherwise they get tiles of CARAMEL_OPT_MEDIUM_TILE_VECS
+   * (default 1024) and launches like the small units'. */
+  CARAMEL_OPT_LONG_LAUNCH_BYTES = 15,
+  CARAMEL_OPT_MEDIUM_TILE_VECS = 16
 };
 enum { CARAMEL_LAUNCH_PER_UNIT = 0, CARAMEL_LAUNCH_PER_STREAM = 1, CARAMEL_LAUNCH_AUTO = 2 };
 enum { CARAMEL_BATCH_STAGED = 0, CARAMEL_BATCH_DIRECT = 1 };

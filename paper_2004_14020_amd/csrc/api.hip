@@ -47,7 +47,6 @@ struct Options {
   uint32_t unroll = 0;
   uint32_t block = 1024;        // workgroup of launches over large units
   uint32_t small_block = 256;   // ... over everything else
-  uint32_t lane_by_class = 0;   // pipeline: large units on the caller's stream, small ones on the internal one
   uint32_t stream_major = 4;    // vectors per lane of the stream-major kernel for large units (0 = off)
   uint64_t launch_min_bytes = 4u << 20;         // small units share a launch up to this size
   uint64_t large_launch_min_bytes = 64u << 20;  // large units likewise
@@ -61,7 +60,8 @@ constexpr unsigned kOrderOnly = hipEventDisableTiming | hipEventDisableSystemFen
 struct LaunchGroup {
   uint32_t stream, first_unit;
   Range reduce, copy;
-  bool large;  // made of large units only: large tiles, large workgroups
+  bool large;  // made of large units only: large workgroups
+  bool lng;    // ... in a stream with enough of them for long launches: large tiles, stream-major kernel
 };
 
 struct TimedLaunch {
@@ -170,7 +170,7 @@ struct Timed {
   }
 };
 
-int run_reduce(caramel_plan* p, bool direct, Range r, bool large, hipStream_t s) {
+int run_reduce(caramel_plan* p, bool direct, Range r, bool large, bool lng, hipStream_t s) {
   if (r.count == 0) return CARAMEL_OK;
   ReduceArgs a{};
   a.tiles = direct ? p->d_direct : p->d_staged;
@@ -183,9 +183,10 @@ int run_reduce(caramel_plan* p, bool direct, Range r, bool large, hipStream_t s)
   a.tree = p->host.cfg.pattern == CARAMEL_PATTERN_HALVING_DOUBLING;
   // by default a workgroup takes its tile in one go: vectors per lane = tile / workgroup size
   a.block = large ? p->opt.block : p->opt.small_block;
-  const uint32_t tile_vecs = large ? p->opt.shape.large_vecs : p->opt.shape.small_vecs;
+  const uint32_t tile_vecs =
+      !large ? p->opt.shape.small_vecs : (lng ? p->opt.shape.large_vecs : p->opt.shape.medium_vecs);
   a.unroll = p->opt.unroll ? p->opt.unroll : std::max(1u, tile_vecs / a.block);
-  a.stream_major = large ? p->opt.stream_major : 0;
+  a.stream_major = lng ? p->opt.stream_major : 0;
   a.max_grid = p->opt.max_grid;
   Timed timer(p, CARAMEL_K_REDUCE, s);
   HIP_TRY(launch_ring_reduce(a, s));
@@ -262,20 +263,24 @@ const std::vector<LaunchGroup>& launch_groups(caramel_plan* p, bool direct) {
   if (mode == CARAMEL_LAUNCH_AUTO) mode = pipelined ? CARAMEL_LAUNCH_PER_UNIT : CARAMEL_LAUNCH_PER_STREAM;
   const uint64_t es = p->host.elem_size();
   // Without the pipeline both plan streams run on the caller's stream: treat them as one.
-  const bool by_class = pipelined && p->opt.lane_by_class;
-  const uint32_t lanes = (pipelined && !by_class) ? p->host.cfg.num_streams : 1;
+  const uint32_t lanes = pipelined ? p->host.cfg.num_streams : 1;
   for (int cls = 0; cls < 2; ++cls) {
-    const uint64_t min_bytes = cls == kLarge ? p->opt.large_launch_min_bytes : p->opt.launch_min_bytes;
     for (uint32_t lane = 0; lane < lanes; ++lane) {
       LaunchGroup g{};
       uint64_t bytes = 0;
       bool open = false;
       for (uint32_t s = 0; s < p->host.cfg.num_streams; ++s) {
-        if (pipelined && !by_class && s != lane) continue;
+        if (pipelined && s != lane) continue;
+        const bool lng = cls == kLarge && tt.long_launches[s];
+        const uint64_t min_bytes = lng ? p->opt.large_launch_min_bytes : p->opt.launch_min_bytes;
+        // tiles of a long-launch stream and of another stream differ in shape: never one launch
+        if (open && g.lng != lng) {
+          out.push_back(g);
+          open = false;
+        }
         for (uint32_t u : tt.order[cls][s]) {
           if (!open) {
-            const uint32_t on = by_class ? uint32_t(cls) : lane;
-            g = LaunchGroup{on, u, Range{unit_tiles[u].begin, 0}, Range{tt.copy_unit[u].begin, 0}, cls == kLarge};
+            g = LaunchGroup{lane, u, Range{unit_tiles[u].begin, 0}, Range{tt.copy_unit[u].begin, 0}, cls == kLarge, lng};
             bytes = 0;
             open = true;
           }
@@ -313,7 +318,7 @@ int pipeline(caramel_plan* p, hipStream_t user, bool with_copies, bool direct) {
   for (const LaunchGroup& g : launch_groups(p, direct)) {
     hipStream_t s = lane[g.stream];
     if (copies) rc = run_copy(p, false, g.copy, s);
-    if (!rc) rc = run_reduce(p, direct, g.reduce, g.large, s);
+    if (!rc) rc = run_reduce(p, direct, g.reduce, g.large, g.lng, s);
     if (!rc && copies) rc = run_copy(p, true, g.copy, s);
     if (rc) break;
   }
@@ -491,10 +496,6 @@ int caramel_plan_set_option(caramel_plan* p, uint32_t option, uint64_t value) {
       if (value != 256 && value != 512 && value != 1024) return fail(CARAMEL_EINVAL, "block must be 256, 512 or 1024");
       p->opt.small_block = uint32_t(value);
       return CARAMEL_OK;
-    case 14:  // experimental: lane by class
-      p->opt.lane_by_class = value ? 1 : 0;
-      p->groups_stale[0] = p->groups_stale[1] = true;
-      return CARAMEL_OK;
     case CARAMEL_OPT_LARGE_LAUNCH_MIN_BYTES:
       p->opt.large_launch_min_bytes = value;
       p->groups_stale[0] = p->groups_stale[1] = true;
@@ -502,6 +503,13 @@ int caramel_plan_set_option(caramel_plan* p, uint32_t option, uint64_t value) {
     case CARAMEL_OPT_STREAM_MAJOR:
       if (value != 0 && value != 2 && value != 4) return fail(CARAMEL_EINVAL, "stream_major must be 0, 2 or 4");
       p->opt.stream_major = uint32_t(value);
+      return CARAMEL_OK;
+    case CARAMEL_OPT_MEDIUM_TILE_VECS:
+      if (value < 64 || value > (1u << 20)) return fail(CARAMEL_EINVAL, "tile_vecs must be in [64, 2^20]");
+      p->opt.shape.medium_vecs = uint32_t(value);
+      return CARAMEL_OK;
+    case CARAMEL_OPT_LONG_LAUNCH_BYTES:
+      p->opt.shape.long_bytes = value;
       return CARAMEL_OK;
     case CARAMEL_OPT_LARGE_UNIT_BYTES:
       p->opt.shape.large_bytes = value;
@@ -567,13 +575,13 @@ int caramel_bind(caramel_plan* p, void* const* grads, void* fused_ws) {
     if (p->streams[s]) HIP_TRY(hipStreamSynchronize(p->streams[s]));
   release_device(p);
 
-  build_tiles(h, p->opt.shape, p->tt);
-  p->groups_stale[0] = p->groups_stale[1] = true;
   std::vector<uint64_t> rows((n + 1) * W, 0);
   for (uint32_t w = 0; w < W; ++w) {
     for (size_t t = 0; t < n; ++t) rows[t * W + w] = reinterpret_cast<uint64_t>(grads[w * n + t]);
     rows[n * W + w] = fused_ws ? reinterpret_cast<uint64_t>(fused_ws) + uint64_t(w) * h.fused_elems * es : 0;
   }
+  build_tiles(h, p->opt.shape, p->tt, rows.data());
+  p->groups_stale[0] = p->groups_stale[1] = true;
   int rc = upload(rows, &p->d_rows);
   if (!rc) rc = upload(p->tt.direct, &p->d_direct);
   if (!rc && fused_ws) rc = upload(p->tt.staged, &p->d_staged);

@@ -20,7 +20,7 @@ void cut_run(std::vector<ReduceTile>& out, uint32_t row, uint32_t first, uint64_
 
 }  // namespace
 
-void build_tiles(const HostPlan& p, const TileShape& ts, TileTables& out) {
+void build_tiles(const HostPlan& p, const TileShape& ts, TileTables& out, const uint64_t* row_addr) {
   out = TileTables{};
   const uint32_t W = p.cfg.world;
   const uint64_t ve = 16 / p.elem_size();  // elements per 16-byte vector
@@ -30,8 +30,23 @@ void build_tiles(const HostPlan& p, const TileShape& ts, TileTables& out) {
   out.staged_unit.resize(nu);
   out.direct_unit.resize(nu);
   out.copy_unit.resize(nu);
-  for (uint32_t ui = 0; ui < nu; ++ui)
-    out.order[is_large_unit(p, ui, ts) ? kLarge : kSmall][p.units[ui].stream].push_back(ui);
+  uint64_t large_total[2] = {0, 0};
+  bool aligned[2] = {true, true};
+  const uint64_t tile_bytes = uint64_t(ts.large_vecs) * 16;
+  for (uint32_t ui = 0; ui < nu; ++ui) {
+    const bool large = is_large_unit(p, ui, ts);
+    const uint32_t s = p.units[ui].stream;
+    out.order[large ? kLarge : kSmall][s].push_back(ui);
+    if (!large) continue;
+    large_total[s] += p.units[ui].elems * p.elem_size();
+    if (row_addr) {
+      const caramel_entry& e = p.entries[p.units[ui].first_entry];
+      for (uint32_t w = 0; w < W; ++w)
+        if ((row_addr[size_t(e.tensor) * W + w] + e.tensor_off * p.elem_size()) % tile_bytes) aligned[s] = false;
+    }
+  }
+  for (int s = 0; s < 2; ++s)
+    out.long_launches[s] = large_total[s] >= ts.long_bytes && large_total[s] > 0 && aligned[s];
 
   for (int cls = 0; cls < 2; ++cls)
     for (uint32_t s = 0; s < p.cfg.num_streams; ++s)
@@ -39,7 +54,8 @@ void build_tiles(const HostPlan& p, const TileShape& ts, TileTables& out) {
         const caramel_unit& u = p.units[ui];
         const uint64_t* seg = p.segments(ui);
         const caramel_entry* ent = &p.entries[u.first_entry];
-        const uint64_t tile_elems = uint64_t(cls == kLarge ? ts.large_vecs : ts.small_vecs) * ve;
+        const uint64_t tile_elems =
+            uint64_t(cls == kSmall ? ts.small_vecs : (out.long_launches[s] ? ts.large_vecs : ts.medium_vecs)) * ve;
         out.staged_unit[ui].begin = uint32_t(out.staged.size());
         out.direct_unit[ui].begin = uint32_t(out.direct.size());
         out.copy_unit[ui].begin = uint32_t(out.copy.size());

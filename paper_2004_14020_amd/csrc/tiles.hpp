@@ -34,9 +34,11 @@ struct Range {
 };
 
 struct TileShape {
-  uint32_t large_vecs = 4096;        // vectors per reduce tile of a large chunk unit
+  uint32_t large_vecs = 4096;        // vectors per reduce tile of a large chunk unit (long launches)
+  uint32_t medium_vecs = 1024;       // ... when a stream has too few large units for long launches
   uint32_t small_vecs = 256;         // ... of every other unit
   uint64_t large_bytes = 4u << 20;   // a chunk unit of at least this many bytes per replica is "large"
+  uint64_t long_bytes = 64u << 20;   // a stream whose large units total at least this much gets long launches
   uint32_t copy_vecs = 512;          // vectors per copy tile
 };
 
@@ -58,9 +60,13 @@ struct TileTables {
   // tiles of consecutive units of one class and stream are adjacent, and so are all tiles of
   // one class.
   std::vector<uint32_t> order[2][2];  // [class][stream] -> unit indices
+  bool long_launches[2] = {false, false};  // per stream: large units use large_vecs tiles (else medium_vecs)
   std::vector<Range> staged_unit, direct_unit, copy_unit;  // tile range of every unit
 };
 
-void build_tiles(const HostPlan& p, const TileShape& ts, TileTables& out);
+// `row0_addr`, if given, holds (n_tensors x W) base addresses, tensor-major: large tiles are used
+// for a stream only if every large unit of it starts on a multiple of the large tile size in
+// every replica (the stream-major kernel is markedly slower on misaligned runs).
+void build_tiles(const HostPlan& p, const TileShape& ts, TileTables& out, const uint64_t* row_addr = nullptr);
 
 }  // namespace caramel

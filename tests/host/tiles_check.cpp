@@ -37,6 +37,8 @@ static void check_case(const caramel_config& cfg, const std::vector<uint64_t>& e
   shape.large_vecs = tile_vecs;
   shape.small_vecs = small_vecs;
   shape.large_bytes = large_bytes;
+  shape.long_bytes = (large_bytes % 3 == 0) ? 0 : 200000;
+  shape.medium_vecs = 128;
   shape.copy_vecs = copy_vecs;
   build_tiles(p, shape, tt);
   const uint64_t es = p.elem_size(), ve = 16 / es, W = cfg.world;
@@ -57,7 +59,7 @@ static void check_case(const caramel_config& cfg, const std::vector<uint64_t>& e
       total_tiles += r.count;
       for (uint32_t i = r.begin; i < r.begin + r.count; ++i) {
         const ReduceTile& t = tiles[i];
-        CHECK(t.n_elems > 0 && t.n_elems <= uint64_t(is_large_unit(p, u, shape) ? tile_vecs : small_vecs) * ve);
+        CHECK(t.n_elems > 0 && t.n_elems <= uint64_t(!is_large_unit(p, u, shape) ? small_vecs : (tt.long_launches[un.stream] ? tile_vecs : shape.medium_vecs)) * ve);
         CHECK(t.first < W);
         CHECK(t.row <= fused_row);
         const uint64_t e0 = uint64_t(t.vec_off) * ve, e1 = e0 + t.n_elems;

@@ -84,8 +84,9 @@ def test_allreduce_all_modes(W, dtype, launch, batch, streams):
     {cm.OPT_MAX_GRID: 7}, {cm.OPT_NONTEMPORAL: 0}, {cm.OPT_UNROLL: 2, cm.OPT_MAX_GRID: 300},
     {cm.OPT_LAUNCH_MIN_BYTES: 1 << 16}, {cm.OPT_LAUNCH_MIN_BYTES: 1 << 30, cm.OPT_BATCH_PATH: cm.BATCH_STAGED},
     {cm.OPT_LAUNCH_MIN_BYTES: 200000, cm.OPT_BATCH_PATH: cm.BATCH_STAGED},
-    {cm.OPT_STREAM_MAJOR: 4, cm.OPT_LARGE_UNIT_BYTES: 0, cm.OPT_TILE_VECS: 4096}, {cm.OPT_STREAM_MAJOR: 2, cm.OPT_LARGE_UNIT_BYTES: 0, cm.OPT_TILE_VECS: 512, cm.OPT_BLOCK: 256},
-    {cm.OPT_STREAM_MAJOR: 4, cm.OPT_LARGE_UNIT_BYTES: 65536, cm.OPT_TILE_VECS: 1024, cm.OPT_BLOCK: 256, cm.OPT_BATCH_PATH: cm.BATCH_STAGED},
+    {cm.OPT_STREAM_MAJOR: 4, cm.OPT_LARGE_UNIT_BYTES: 0, cm.OPT_LONG_LAUNCH_BYTES: 0, cm.OPT_TILE_VECS: 4096}, {cm.OPT_STREAM_MAJOR: 2, cm.OPT_LARGE_UNIT_BYTES: 0, cm.OPT_LONG_LAUNCH_BYTES: 0, cm.OPT_TILE_VECS: 512, cm.OPT_BLOCK: 256},
+    {cm.OPT_STREAM_MAJOR: 4, cm.OPT_LARGE_UNIT_BYTES: 65536, cm.OPT_LONG_LAUNCH_BYTES: 1, cm.OPT_TILE_VECS: 1024, cm.OPT_BLOCK: 256, cm.OPT_BATCH_PATH: cm.BATCH_STAGED},
+    {cm.OPT_LARGE_UNIT_BYTES: 0, cm.OPT_LONG_LAUNCH_BYTES: 0}, {cm.OPT_LARGE_UNIT_BYTES: 0, cm.OPT_LONG_LAUNCH_BYTES: 100000, cm.OPT_MEDIUM_TILE_VECS: 512},
     {cm.OPT_LARGE_UNIT_BYTES: 0}, {cm.OPT_LARGE_UNIT_BYTES: 1 << 40}, {cm.OPT_LARGE_UNIT_BYTES: 100000, cm.OPT_SMALL_TILE_VECS: 64},
     {cm.OPT_LARGE_UNIT_BYTES: 65536, cm.OPT_SMALL_BLOCK: 512, cm.OPT_SMALL_TILE_VECS: 1024, cm.OPT_BATCH_PATH: cm.BATCH_STAGED},
     {cm.OPT_BLOCK: 256}, {cm.OPT_BLOCK: 1024, cm.OPT_TILE_VECS: 2048}, {cm.OPT_BLOCK: 1024, cm.OPT_TILE_VECS: 128},
