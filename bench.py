@@ -138,7 +138,8 @@ def main() -> int:
     alg_bytes = wl.algorithmic_bytes()
     gbs = alg_bytes / (ms_per_step * 1e-3) / 1e9
 
-    # Dominant kernel: k_ring_reduce (in the default direct mode it is the only kernel).  The
+    # Dominant kernels: the two variants of the ring-reduce kernel (stream-major for long launches
+    # over large units, all-at-once for the rest); in the default direct mode nothing else runs.  The
     # library brackets everything each internal stream does in a call with one pair of HIP events
     # recorded on that stream; launches of one stream run back to back, so a launch's average
     # duration is the stream's busy time divided by its launches.  The two streams overlap in
@@ -156,7 +157,7 @@ def main() -> int:
     achieved = alg_bytes / (span_ms * 1e-3) / 1e9
     traffic = read_traffic(wl.name)
     roofline = {
-        "bound": "hbm", "kernel": "k_ring_reduce", "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS,
+        "bound": "hbm", "kernel": "k_ring_reduce_sm (large units) + k_ring_reduce (others)", "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS,
         "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": traffic,
         "launches_per_step": launches_per_step, "avg_launch_ms": round(avg_ms, 6),
         "bytes_per_launch": round(bytes_per_launch), "per_launch_achieved": round(per_launch, 1),
