@@ -193,3 +193,18 @@ def test_net_model_fit():
     assert a == pytest.approx(float(fa), rel=1e-9) and b == pytest.approx(float(fb), rel=1e-12)
     with pytest.raises(cm.CaramelError):
         cm.net_model_fit(64, 1.0, 64, 2.0)
+
+
+def test_header_is_plain_c_and_the_library_links_from_c(tmp_path):
+    """include/caramel.h compiled as strict C99, linked against the shared library, host-only calls."""
+    import shutil
+    import subprocess
+    if shutil.which("gcc") is None:
+        pytest.skip("gcc not available")
+    exe = str(tmp_path / "c_abi_check")
+    libdir = os.path.dirname(binding.LIB_PATH)
+    subprocess.run(["gcc", "-std=c99", "-pedantic", "-Wall", "-Wextra", "-Werror", "-I", os.path.join(ROOT, "include"),
+                    os.path.join(ROOT, "tests", "host", "c_abi_check.c"), "-L", libdir, "-l:libcaramel.so",
+                    "-Wl,-rpath," + libdir, "-o", exe], check=True)
+    res = subprocess.run([exe], capture_output=True, text=True, timeout=120)
+    assert res.returncode == 0 and "c_abi_check ok" in res.stdout, res.stdout + res.stderr
