@@ -11,10 +11,12 @@ import pytest
 import oracle
 import oracle.aggregate
 import oracle.plan
+import oracle.schedule
 
 import test_oracle_aggregate as pins_agg
 import test_oracle_patterns as pins_pat
 import test_oracle_plan as pins_plan
+import test_oracle_schedule as pins_sched
 import test_oracle_timed as pins_timed
 
 ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
@@ -50,6 +52,16 @@ AGG_PINS = [
     pins_timed.test_schedule_invariants,
     pins_timed.test_threshold_by_brute_force_scan_and_closed_form,
 ]
+SCHED_PINS = [
+    pins_sched.test_hand_walked_example,
+    pins_sched.test_invariants_on_random_cases,
+    pins_sched.test_integer_cases_against_a_time_step_search,
+    pins_sched.test_everything_fits_behind_the_backward_pass_start,
+    pins_sched.test_nothing_fits_beside_the_computation,
+    pins_sched.test_forward_window_is_the_mirror_image_of_the_backward_window,
+    pins_sched.test_a_later_boundary_is_respected_even_when_earlier_room_is_free,
+    pins_sched.test_windows_of_a_batch_come_from_its_last_updated_and_first_read_member,
+]
 
 # (file, text to replace, replacement, what the mistake is)
 MUTATIONS = [
@@ -79,6 +91,22 @@ MUTATIONS = [
     ("aggregate.py", "    return (bits.astype(np.uint32) << np.uint32(16)).view(np.float32)", "    return (bits.astype(np.uint32) << np.uint32(15)).view(np.float32)", "wrong widening shift"),
     ("aggregate.py", "            region[...] = 0\n", "", "padding not cleared"),
     ("aggregate.py", "                region[e.unit_off:e.unit_off + e.elems] = \\\n                    grads[w][e.tensor][e.tensor_off:e.tensor_off + e.elems]", "                region[e.unit_off:e.unit_off + e.elems] = \\\n                    grads[0][e.tensor][e.tensor_off:e.tensor_off + e.elems]", "pack reads worker 0 for every replica"),
+    ("schedule.py", "key=lambda g: (-nbytes[g], g))", "key=lambda g: (nbytes[g], g))", "groups taken smallest first"),
+    ("schedule.py", "key=lambda g: (-nbytes[g], g))", "key=lambda g: g)", "groups taken in queue order"),
+    ("schedule.py", "        s = _earliest_start(slots, ready[g], dur[g], bp_len)\n        if s is not None:\n            slots[g] = Slot(BIN_BACKWARD, s, s + dur[g], 2)\n            continue\n        e = _latest_end(slots, need[g], dur[g], 0.0)\n        if e is not None:\n            slots[g] = Slot(BIN_FORWARD, e - dur[g], e, 2)\n",
+     "        e = _latest_end(slots, need[g], dur[g], 0.0)\n        if e is not None:\n            slots[g] = Slot(BIN_FORWARD, e - dur[g], e, 2)\n            continue\n        s = _earliest_start(slots, ready[g], dur[g], bp_len)\n        if s is not None:\n            slots[g] = Slot(BIN_BACKWARD, s, s + dur[g], 2)\n", "forward pass tried before the backward pass"),
+    ("schedule.py", "        if cost_bp <= cost_fp:", "        if cost_bp < cost_fp:", "equal cost resolved towards the forward pass"),
+    ("schedule.py", "        if cost_bp <= cost_fp:", "        if cost_bp >= cost_fp:", "the side that adds MORE time is taken"),
+    ("schedule.py", "        cost_bp = max(0.0, (s + dur[g]) - bp_end)", "        cost_bp = max(0.0, (s + dur[g]) - bp_len)", "overrun measured from the unextended backward pass"),
+    ("schedule.py", "        cost_fp = max(0.0, fp_begin - (e - dur[g]))", "        cost_fp = dur[g]", "forward cost taken as the whole transfer time"),
+    ("schedule.py", "    return max(good) if good else None", "    return min(good) if good else None", "forward slots packed from the start of the pass"),
+    ("schedule.py", "    cands = [float(ready)] + [s.end for s in placed if s is not None and s.bin == BIN_BACKWARD and s.end >= ready]", "    cands = [0.0] + [s.end for s in placed if s is not None and s.bin == BIN_BACKWARD]", "backward boundary ignored"),
+    ("schedule.py", "    return all(not (s.start < end and start < s.end) for s in placed if s is not None and s.bin == which)", "    return all(not (s.start <= end and start <= s.end) for s in placed if s is not None and s.bin == which)", "touching transfers treated as overlapping"),
+    ("schedule.py", "    return all(not (s.start < end and start < s.end) for s in placed if s is not None and s.bin == which)", "    return all(not (s.start < end and start < s.end) for s in placed if s is not None)", "the two windows share one timeline"),
+    ("schedule.py", "    dur = [net_a + net_b * float(b) for b in nbytes]", "    dur = [net_b * float(b) for b in nbytes]", "fixed cost per transfer dropped"),
+    ("schedule.py", "        ready.append(max(ready_time[t] for t in members))", "        ready.append(min(ready_time[t] for t in members))", "batch boundary from its first updated member"),
+    ("schedule.py", "        need.append(min(read_time[t] for t in members))", "        need.append(max(read_time[t] for t in members))", "batch boundary from its last read member"),
+    ("schedule.py", "    overlap = (comm + compute - total) / lesser if lesser > 0.0 else 0.0", "    overlap = (comm + compute - total) / compute if lesser > 0.0 else 0.0", "overlap normalised by the computation time only"),
 ]
 
 
@@ -87,7 +115,7 @@ def load_variant(fname, old, new):
     pkg = types.ModuleType("oracle_variant")
     pkg.__path__ = []
     mods = {}
-    for name in ("plan.py", "aggregate.py", "ring_sim.py"):
+    for name in ("plan.py", "aggregate.py", "ring_sim.py", "schedule.py"):
         with open(os.path.join(ROOT, "oracle", name)) as f:
             src = f.read()
         if name == fname:
@@ -110,15 +138,21 @@ def install(monkeypatch, mods):
         for k, v in vars(mod).items():
             if not k.startswith("_") and callable(v) and getattr(v, "__module__", "").startswith("oracle_variant"):
                 exported[k] = v
-    for target in (oracle, oracle.plan, oracle.aggregate, pins_plan, pins_agg, pins_pat, pins_timed):
+    for target in (oracle, oracle.plan, oracle.aggregate, oracle.schedule, pins_plan, pins_agg, pins_pat, pins_timed, pins_sched):
         for k, v in exported.items():
             if hasattr(target, k):
                 monkeypatch.setattr(target, k, v)
 
 
-def run_pins():
+def run_pins(fname=None):
+    """All pins, or only those that look at the edited file."""
+    pins = PLAN_PINS + AGG_PINS + SCHED_PINS
+    if fname == "schedule.py":
+        pins = SCHED_PINS
+    elif fname is not None:
+        pins = PLAN_PINS + AGG_PINS
     failed = []
-    for pin in PLAN_PINS + AGG_PINS:
+    for pin in pins:
         try:
             pin()
         except AssertionError:
@@ -136,4 +170,4 @@ def test_harness_passes_on_the_undamaged_oracle(monkeypatch):
 @pytest.mark.parametrize("fname,old,new,what", MUTATIONS, ids=[m[3] for m in MUTATIONS])
 def test_planted_mistake_is_caught(monkeypatch, fname, old, new, what):
     install(monkeypatch, load_variant(fname, old, new))
-    assert run_pins(), f"no pin noticed: {what}"
+    assert run_pins(fname), f"no pin noticed: {what}"
