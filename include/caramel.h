@@ -147,6 +147,59 @@ int caramel_plan_times(const caramel_plan* plan, double* enqueue, double* start,
 int caramel_net_model_fit(uint64_t bytes1, double time1, uint64_t bytes2, double time2, double* a, double* b);
 int caramel_threshold_estimate(double a, double b, uint64_t* threshold_bytes);
 
+/* ---- transfer scheduler: host only (section 4.3) ---------------------------------------- */
+
+/* Where the scheduler puts one group's transfer.  Backward-pass times count from the start of
+ * the backward pass; forward-pass times from the start of the next forward pass and are
+ * negative where the transfer begins before it. */
+enum { CARAMEL_BIN_BACKWARD = 0, CARAMEL_BIN_FORWARD = 1 };
+typedef struct caramel_slot {
+  uint32_t bin;   /* CARAMEL_BIN_BACKWARD or CARAMEL_BIN_FORWARD */
+  uint32_t stage; /* 2: placed beside the computation; 3: placed where it lengthens the iteration */
+  double start;
+  double end;
+} caramel_slot;
+
+/* Totals of a schedule.  N = comm_time, C = compute_time, T = iteration_time are tied by the
+ * relation of section 3: T = C + N - overlap * min(N, C), utilization = C / T. */
+typedef struct caramel_schedule_summary {
+  double comm_time;      /* sum of all transfer times */
+  double compute_time;   /* bp_len + fp_len */
+  double bp_overrun;     /* how far transfers run past the end of the backward pass */
+  double fp_overrun;     /* how long before the start of the forward pass they begin */
+  double iteration_time; /* compute_time + bp_overrun + fp_overrun */
+  double overlap;        /* overlap coefficient, 0 when there is no transfer or no computation */
+  double utilization;
+} caramel_schedule_summary;
+
+/* Greedy packing of section 4.3.  n_groups transfers of group_bytes[g] bytes; group g may not
+ * start before ready[g] (backward pass, when the last of its members has been updated) and, if
+ * it is moved to the forward pass, must end by need[g] (when the first of its members is read).
+ * A transfer of d bytes occupies the network for net_a + net_b * d; transfers of one window may
+ * touch but not overlap.  Groups are taken largest first (equal sizes in index order).  Each is
+ * placed in the backward pass at the earliest free start >= ready[g] if it then ends by bp_len;
+ * else in the forward pass at the latest free end <= need[g] if it then starts at or after 0;
+ * else it is left over.  Left-over groups are taken again in the same order with both limits
+ * lifted, and go to the side that lengthens the iteration less (how far the slot pushes the end
+ * of the backward window, already extended by earlier slots, out, against how far it pushes the
+ * start of the forward window back; equal: backward pass).
+ *   slots    n_groups records, written in the caller's group order (host memory, caller's);
+ *   summary  may be NULL.
+ * All arithmetic is in IEEE doubles in the order stated above.  EINVAL: NULL array with
+ * n_groups > 0; a negative or NaN length or coefficient; ready[g] outside [0, bp_len]; need[g]
+ * outside [0, fp_len]; a transfer time that is not positive. */
+int caramel_schedule_transfers(const uint64_t* group_bytes, const double* ready, const double* need,
+                               uint32_t n_groups, double bp_len, double fp_len, double net_a, double net_b,
+                               caramel_slot* slots, caramel_schedule_summary* summary);
+
+/* Transfer boundaries of a plan's units (section 4.3: a batch is bound by its member that is
+ * updated last and by its member that is read first).  ready_time / read_time: n_tensors values
+ * each, indexed like the tensor list given to caramel_plan_create.  Outputs: `cap` entries
+ * each, one per unit, any may be NULL; group_bytes[u] = elems * element size.  EINVAL if cap is
+ * smaller than the unit count or an input is NULL. */
+int caramel_plan_windows(const caramel_plan* plan, const double* ready_time, const double* read_time,
+                         uint64_t* group_bytes, double* ready, double* need, uint32_t cap);
+
 /* Free host and device tables and internal streams/events.  NULL is allowed. */
 void caramel_plan_destroy(caramel_plan* plan);
 

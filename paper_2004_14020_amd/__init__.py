@@ -4,11 +4,11 @@ The work is done by hand-written HIP kernels behind the C ABI declared in
 include/caramel.h; this package only marshals arguments (binding.py) and, in
 device.py, uses PyTorch to hold device memory and streams.
 """
-from .binding import (BATCH_DIRECT, BATCH_STAGED, BF16, F32, K_COUNT, K_PACK, K_REDUCE, K_SEQUENCE, K_UNPACK,
+from .binding import (BIN_BACKWARD, BIN_FORWARD, BATCH_DIRECT, BATCH_STAGED, BF16, F32, K_COUNT, K_PACK, K_REDUCE, K_SEQUENCE, K_UNPACK,
                       KIND_BATCH, KIND_CHUNK, LAUNCH_AUTO, LAUNCH_PER_STREAM, LAUNCH_PER_UNIT, OPT_BATCH_PATH,
                       PATTERN_HALVING_DOUBLING, PATTERN_RING, PATTERN_SHUFFLE, OPT_BLOCK, OPT_LAUNCH_MIN_BYTES, OPT_LAUNCH_MODE, OPT_PIPELINE_MIN_BYTES, OPT_SMALL_TILE_VECS, OPT_SMALL_BLOCK, OPT_LARGE_UNIT_BYTES, OPT_STREAM_MAJOR, OPT_LARGE_LAUNCH_MIN_BYTES, OPT_LONG_LAUNCH_BYTES, OPT_MEDIUM_TILE_VECS, OPT_MAX_GRID, OPT_NONTEMPORAL, OPT_TILE_VECS, OPT_UNROLL,
-                      SPLIT_ADAPTIVE, SPLIT_FIXED, SPLIT_NONE, CaramelError, Config, Entry, Plan, Unit, lib,
-                      net_model_fit, threshold_estimate)
+                      SPLIT_ADAPTIVE, SPLIT_FIXED, SPLIT_NONE, CaramelError, Config, Entry, Plan, ScheduleSummary, Slot,
+                      Unit, lib, net_model_fit, schedule_transfers, threshold_estimate)
 
 
 # Functional spellings with the names of the C entry points.
@@ -30,6 +30,14 @@ def caramel_net_model_fit(bytes1, time1, bytes2, time2):
 
 def caramel_threshold_estimate(a, b) -> int:
     return threshold_estimate(a, b)
+
+
+def caramel_schedule_transfers(group_bytes, ready, need, bp_len, fp_len, net_a, net_b):
+    return schedule_transfers(group_bytes, ready, need, bp_len, fp_len, net_a, net_b)
+
+
+def caramel_plan_windows(plan: Plan, ready_time, read_time):
+    return plan.windows(ready_time, read_time)
 
 
 def caramel_plan_destroy(plan: Plan) -> None:

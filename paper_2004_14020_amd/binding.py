@@ -14,6 +14,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(HERE, "libcaramel.so")
 
 OK, EINVAL, ENOMEM, EHIP, ESTATE = 0, 1, 2, 3, 4
+BIN_BACKWARD, BIN_FORWARD = 0, 1
 F32, BF16 = 0, 1
 SPLIT_NONE, SPLIT_FIXED, SPLIT_ADAPTIVE = 0, 1, 2
 KIND_BATCH, KIND_CHUNK = 0, 1
@@ -26,7 +27,7 @@ K_PACK, K_REDUCE, K_UNPACK, K_SEQUENCE, K_COUNT = 0, 1, 2, 3, 4
 
 EXPORTS = (
     "caramel_plan_create", "caramel_plan_create_timed", "caramel_plan_times", "caramel_net_model_fit",
-    "caramel_threshold_estimate", "caramel_plan_destroy", "caramel_plan_counts", "caramel_plan_units",
+    "caramel_threshold_estimate", "caramel_schedule_transfers", "caramel_plan_windows", "caramel_plan_destroy", "caramel_plan_counts", "caramel_plan_units",
     "caramel_plan_entries", "caramel_plan_segments", "caramel_plan_serialize", "caramel_bind",
     "caramel_pack", "caramel_ring_reduce", "caramel_unpack", "caramel_allreduce",
     "caramel_plan_set_option", "caramel_profile", "caramel_profile_read", "caramel_last_error",
@@ -49,6 +50,16 @@ class Unit(C.Structure):
 class Entry(C.Structure):
     _fields_ = [("tensor", C.c_uint32), ("unit", C.c_uint32), ("tensor_off", C.c_uint64),
                 ("unit_off", C.c_uint64), ("elems", C.c_uint64)]
+
+
+class Slot(C.Structure):
+    _fields_ = [("bin", C.c_uint32), ("stage", C.c_uint32), ("start", C.c_double), ("end", C.c_double)]
+
+
+class ScheduleSummary(C.Structure):
+    _fields_ = [("comm_time", C.c_double), ("compute_time", C.c_double), ("bp_overrun", C.c_double),
+                ("fp_overrun", C.c_double), ("iteration_time", C.c_double), ("overlap", C.c_double),
+                ("utilization", C.c_double)]
 
 
 class KernelStat(C.Structure):
@@ -85,6 +96,10 @@ def lib() -> C.CDLL:
     L.caramel_net_model_fit.argtypes = [C.c_uint64, C.c_double, C.c_uint64, C.c_double,
                                         C.POINTER(C.c_double), C.POINTER(C.c_double)]
     L.caramel_threshold_estimate.argtypes = [C.c_double, C.c_double, C.POINTER(C.c_uint64)]
+    D = C.POINTER(C.c_double)
+    L.caramel_schedule_transfers.argtypes = [C.POINTER(C.c_uint64), D, D, C.c_uint32, C.c_double, C.c_double,
+                                             C.c_double, C.c_double, C.POINTER(Slot), C.POINTER(ScheduleSummary)]
+    L.caramel_plan_windows.argtypes = [P, D, D, C.POINTER(C.c_uint64), D, D, C.c_uint32]
     L.caramel_plan_destroy.argtypes = [P]
     L.caramel_plan_destroy.restype = None
     L.caramel_plan_counts.argtypes = [P, C.POINTER(C.c_uint32), C.POINTER(C.c_uint32), C.POINTER(C.c_uint64)]
@@ -177,6 +192,18 @@ class Plan:
         _check(lib().caramel_plan_times(self._h, bufs[0], bufs[1], bufs[2], n))
         return tuple(list(b[:n]) for b in bufs)
 
+    def windows(self, ready_time: Sequence[float], read_time: Sequence[float]):
+        """(bytes, ready, need) lists, one entry per unit: the units' transfer boundaries."""
+        if len(ready_time) != self.n_tensors or len(read_time) != self.n_tensors:
+            raise ValueError("one update time and one read time per tensor")
+        n = self.counts()[0]
+        rt = (C.c_double * max(1, self.n_tensors))(*[float(t) for t in ready_time])
+        rd = (C.c_double * max(1, self.n_tensors))(*[float(t) for t in read_time])
+        b = (C.c_uint64 * max(1, n))()
+        r, d = (C.c_double * max(1, n))(), (C.c_double * max(1, n))()
+        _check(lib().caramel_plan_windows(self._h, rt, rd, b, r, d, n))
+        return list(b[:n]), list(r[:n]), list(d[:n])
+
     def serialize(self) -> bytes:
         n = C.c_size_t(0)
         _check(lib().caramel_plan_serialize(self._h, None, C.byref(n)))
@@ -221,6 +248,22 @@ def net_model_fit(bytes1: int, time1: float, bytes2: int, time2: float):
     a, b = C.c_double(), C.c_double()
     _check(lib().caramel_net_model_fit(bytes1, time1, bytes2, time2, C.byref(a), C.byref(b)))
     return a.value, b.value
+
+
+def schedule_transfers(group_bytes: Sequence[int], ready: Sequence[float], need: Sequence[float], bp_len: float,
+                       fp_len: float, net_a: float, net_b: float):
+    """(slots, summary): one Slot per group in the caller's order, and the schedule's totals."""
+    n = len(group_bytes)
+    if len(ready) != n or len(need) != n:
+        raise ValueError("one boundary pair per group")
+    b = (C.c_uint64 * max(1, n))(*[int(x) for x in group_bytes])
+    r = (C.c_double * max(1, n))(*[float(x) for x in ready])
+    d = (C.c_double * max(1, n))(*[float(x) for x in need])
+    slots = (Slot * max(1, n))()
+    summary = ScheduleSummary()
+    _check(lib().caramel_schedule_transfers(b, r, d, n, float(bp_len), float(fp_len), float(net_a), float(net_b),
+                                            slots, C.byref(summary)))
+    return list(slots[:n]), summary
 
 
 def threshold_estimate(a: float, b: float) -> int:

@@ -8,7 +8,7 @@ import sys
 HERE = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(HERE)
 LIB = os.path.join(HERE, "libcaramel.so")
-SOURCES = ["plan.cpp", "tiles.cpp", "kernels.hip", "api.hip"]
+SOURCES = ["plan.cpp", "schedule.cpp", "tiles.cpp", "kernels.hip", "api.hip"]
 
 
 def hipcc() -> str:

@@ -14,6 +14,7 @@
 #include "caramel.h"
 #include "kernels.hpp"
 #include "plan.hpp"
+#include "schedule.hpp"
 #include "tiles.hpp"
 
 using namespace caramel;
@@ -381,6 +382,37 @@ int caramel_threshold_estimate(double a, double b, uint64_t* threshold_bytes) {
   if (!threshold_bytes) return fail(CARAMEL_EINVAL, "NULL argument");
   if (!threshold_from_model(a, b, *threshold_bytes))
     return fail(CARAMEL_EINVAL, "need finite a >= 0, b > 0 and a threshold below 2^64");
+  return CARAMEL_OK;
+}
+
+int caramel_schedule_transfers(const uint64_t* group_bytes, const double* ready, const double* need,
+                               uint32_t n_groups, double bp_len, double fp_len, double net_a, double net_b,
+                               caramel_slot* slots, caramel_schedule_summary* summary) {
+  std::string why;
+  try {
+    const int rc = schedule_transfers(group_bytes, ready, need, n_groups, bp_len, fp_len, net_a, net_b, slots,
+                                      summary, why);
+    return rc == CARAMEL_OK ? rc : fail(rc, why.c_str());
+  } catch (const std::bad_alloc&) {
+    return fail(CARAMEL_ENOMEM, "out of host memory");
+  }
+}
+
+int caramel_plan_windows(const caramel_plan* plan, const double* ready_time, const double* read_time,
+                         uint64_t* group_bytes, double* ready, double* need, uint32_t cap) {
+  if (!plan || !ready_time || !read_time) return fail(CARAMEL_EINVAL, "NULL argument");
+  const size_t n = plan->host.units.size();
+  if (cap < n) return fail(CARAMEL_EINVAL, "cap is smaller than the number of units");
+  try {
+    std::vector<uint64_t> b(n);
+    std::vector<double> r(n), d(n);
+    unit_windows(plan->host, ready_time, read_time, b.data(), r.data(), d.data());
+    if (group_bytes) std::copy(b.begin(), b.end(), group_bytes);
+    if (ready) std::copy(r.begin(), r.end(), ready);
+    if (need) std::copy(d.begin(), d.end(), need);
+  } catch (const std::bad_alloc&) {
+    return fail(CARAMEL_ENOMEM, "out of host memory");
+  }
   return CARAMEL_OK;
 }
 

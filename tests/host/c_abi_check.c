@@ -63,6 +63,18 @@ int main(void) {
   CHECK(caramel_net_model_fit(64, 40.0 + 32.0, 4096, 40.0 + 2048.0, &a, &b) == CARAMEL_OK);
   CHECK(a > 39.999 && a < 40.001 && b > 0.4999 && b < 0.5001);
   CHECK(caramel_threshold_estimate(40.0, 0.5, &thr) == CARAMEL_OK && thr == 121);
+  {
+    /* section 4.3: one group fits behind its update time, the other must wait for the forward pass */
+    const uint64_t bytes[2] = {8, 4};
+    const double ready[2] = {6.0, 7.0}, need[2] = {5.0, 4.0};
+    caramel_slot slots[2];
+    caramel_schedule_summary sum;
+    CHECK(caramel_schedule_transfers(bytes, ready, need, 2, 10.0, 5.0, 0.0, 0.5, slots, &sum) == CARAMEL_OK);
+    CHECK(slots[0].bin == CARAMEL_BIN_BACKWARD && slots[0].start == 6.0 && slots[0].end == 10.0);
+    CHECK(slots[1].bin == CARAMEL_BIN_FORWARD && slots[1].start == 2.0 && slots[1].end == 4.0);
+    CHECK(sum.iteration_time == 15.0 && sum.utilization == 1.0);
+    CHECK(caramel_schedule_transfers(bytes, ready, need, 2, 5.0, 5.0, 0.0, 0.5, slots, &sum) == CARAMEL_EINVAL);
+  }
   printf("c_abi_check ok\n");
   return 0;
 }

@@ -12,6 +12,7 @@
 #include <vector>
 
 #include "plan.hpp"
+#include "schedule.hpp"
 #include "tiles.hpp"
 
 using namespace caramel;
@@ -149,8 +150,46 @@ static void check_case(const caramel_config& cfg, const std::vector<uint64_t>& e
   CHECK(std::all_of(fused_seen.begin(), fused_seen.end(), [](uint8_t b) { return b == 1; }));
 }
 
+// The scheduler on random inputs: one slot per group, inside its boundary, no two slots of a
+// window overlapping -- and no out-of-bounds access or undefined behaviour on the way.
+void check_schedule(std::mt19937_64& rng) {
+  const uint32_t n = uint32_t(rng() % 60);
+  const double bp = double(1 + rng() % 40), fp = double(1 + rng() % 40);
+  std::vector<uint64_t> bytes(n);
+  std::vector<double> ready(n), need(n);
+  for (uint32_t g = 0; g < n; ++g) {
+    bytes[g] = 1 + rng() % 5000;
+    ready[g] = bp * double(rng() % 1000) / 999.0;
+    need[g] = fp * double(rng() % 1000) / 999.0;
+    if (ready[g] > bp) ready[g] = bp;
+    if (need[g] > fp) need[g] = fp;
+  }
+  std::vector<caramel_slot> slots(n);
+  caramel_schedule_summary sum{};
+  std::string why;
+  const double a = double(rng() % 4) * 0.25, b = 1e-3 * double(1 + rng() % 8);
+  CHECK(schedule_transfers(bytes.data(), ready.data(), need.data(), n, bp, fp, a, b, slots.data(), &sum, why) ==
+        CARAMEL_OK);
+  for (uint32_t g = 0; g < n; ++g) {
+    const caramel_slot& s = slots[g];
+    CHECK(s.stage == 2 || s.stage == 3);
+    CHECK(s.end > s.start);
+    if (s.bin == CARAMEL_BIN_BACKWARD) {
+      CHECK(s.start >= ready[g] && (s.stage == 3 || s.end <= bp));
+    } else {
+      CHECK(s.bin == CARAMEL_BIN_FORWARD && s.end <= need[g] && (s.stage == 3 || s.start >= 0.0));
+    }
+    for (uint32_t h = 0; h < g; ++h)
+      CHECK(slots[h].bin != s.bin || !(slots[h].start < s.end && s.start < slots[h].end));
+  }
+  CHECK(sum.iteration_time >= sum.compute_time && sum.utilization <= 1.0);
+  CHECK(schedule_transfers(bytes.data(), ready.data(), need.data(), n, -1.0, fp, a, b, slots.data(), &sum, why) ==
+        CARAMEL_EINVAL);
+}
+
 int main() {
   std::mt19937_64 rng(20041402);
+  for (int it = 0; it < 300; ++it) check_schedule(rng);
   auto pick = [&](std::initializer_list<uint64_t> xs) {
     std::vector<uint64_t> v(xs);
     return v[rng() % v.size()];

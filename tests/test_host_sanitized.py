@@ -1,4 +1,4 @@
-"""Host code of the library (planner, tile tables) built with ASan + UBSan and checked on the
+"""Host code of the library (planner, transfer scheduler, tile tables) built with ASan + UBSan and checked on the
 CPU: every tile the kernels will be given stays in bounds and the tables cover every element
 exactly once.  No GPU, no HIP runtime."""
 import os
@@ -18,7 +18,8 @@ def test_planner_and_tile_tables_under_sanitizers(tmp_path):
            "-static-libasan", "-static-libubsan",
            "-I", os.path.join(ROOT, "include"), "-I", CSRC,
            os.path.join(ROOT, "tests", "host", "tiles_check.cpp"),
-           os.path.join(CSRC, "plan.cpp"), os.path.join(CSRC, "tiles.cpp"), "-o", exe]
+           os.path.join(CSRC, "plan.cpp"), os.path.join(CSRC, "schedule.cpp"), os.path.join(CSRC, "tiles.cpp"),
+           "-o", exe]
     subprocess.run(cmd, check=True)
     res = subprocess.run([exe], capture_output=True, text=True, timeout=600)
     assert res.returncode == 0, res.stdout[-2000:] + res.stderr[-2000:]

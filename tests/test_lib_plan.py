@@ -11,6 +11,7 @@ import pytest
 import oracle
 import paper_2004_14020_amd as cm
 from paper_2004_14020_amd import binding
+from workloads import shapes
 from workloads.shapes import ALL, EXTRA, workload
 
 ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
@@ -208,3 +209,89 @@ def test_header_is_plain_c_and_the_library_links_from_c(tmp_path):
                     "-Wl,-rpath," + libdir, "-o", exe], check=True)
     res = subprocess.run([exe], capture_output=True, text=True, timeout=120)
     assert res.returncode == 0 and "c_abi_check ok" in res.stdout, res.stdout + res.stderr
+
+
+# ------------------------------------------------------------------ section 4.3: transfer scheduler
+def same_schedule(got_slots, got_sum, ref):
+    for g, r in zip(got_slots, ref.slots):
+        assert (g.bin, g.stage, g.start, g.end) == (r.bin, r.stage, r.start, r.end)       # same doubles
+    assert (got_sum.comm_time, got_sum.compute_time, got_sum.bp_overrun, got_sum.fp_overrun,
+            got_sum.iteration_time, got_sum.overlap, got_sum.utilization) == \
+           (ref.comm_time, ref.compute_time, ref.bp_overrun, ref.fp_overrun, ref.iteration_time, ref.overlap,
+            ref.utilization)
+
+
+def test_schedule_equals_oracle_on_random_inputs():
+    rng = random.Random(4300)
+    for it in range(600):
+        n = rng.randint(0, 40)
+        bp, fp = rng.random() * 50, rng.random() * 50
+        nbytes = [rng.choice([1, 7, 64, 1000, 4096, 4096, 100000]) * rng.randint(1, 3) for _ in range(n)]
+        whole = it % 3 == 0                       # whole-number times make touching slots and ties common
+        if whole:
+            bp, fp = float(int(bp) + 1), float(int(fp) + 1)
+        ready = [float(rng.randint(0, int(bp))) if whole else rng.random() * bp for _ in range(n)]
+        need = [float(rng.randint(0, int(fp))) if whole else rng.random() * fp for _ in range(n)]
+        a = float(rng.randint(0, 3)) if whole else rng.random() * 3
+        b = rng.choice([1.0 / 1024, 1.0 / 64]) if whole else rng.random() * 1e-3 + 1e-9
+        ref = oracle.schedule_transfers(nbytes, ready, need, bp, fp, a, b)
+        slots, summary = cm.schedule_transfers(nbytes, ready, need, bp, fp, a, b)
+        assert len(slots) == n
+        same_schedule(slots, summary, ref)
+
+
+def test_schedule_golden_example_through_the_library():
+    import json
+    with open(os.path.join(ROOT, "tests", "golden", "transfer_schedule.json")) as f:
+        gold = json.load(f)
+    g = gold["groups"]
+    slots, summary = cm.schedule_transfers([x["bytes"] for x in g], [x["ready"] for x in g], [x["need"] for x in g],
+                                           gold["bp_len"], gold["fp_len"], gold["net_a"], gold["net_b"])
+    bins = {"backward": binding.BIN_BACKWARD, "forward": binding.BIN_FORWARD}
+    for got, want in zip(slots, gold["slots"]):
+        assert (got.bin, got.start, got.end, got.stage) == (bins[want["bin"]], want["start"], want["end"], want["stage"])
+    assert (summary.iteration_time, summary.bp_overrun, summary.fp_overrun) == (28.0, 3.0, 3.0)
+
+
+@pytest.mark.parametrize("name", shapes.ALL + shapes.EXTRA)
+@pytest.mark.parametrize("rho", [0.3, 1.0, 2.5])
+def test_windows_and_schedule_equal_oracle_on_workloads(name, rho):
+    """The units of every workload's plan over the synthetic compute timeline; the per-byte cost
+    of the network model is set so that communication is rho times the computation."""
+    from workloads.timeline import compute_timeline
+    wl = shapes.workload(name)
+    cfg = oracle.Config(wl.world, wl.dtype, wl.batch_threshold_bytes, wl.split_mode, wl.max_depth, wl.split_bytes,
+                        wl.align_bytes, wl.num_streams)
+    ready_time, read_time, bp, fp = compute_timeline(wl)
+    ref_plan = oracle.build_plan(cfg, wl.elems())
+    plan = lib_plan(cfg, wl.elems())
+    want = oracle.group_windows(ref_plan, ready_time, read_time)
+    got = plan.windows(ready_time, read_time)
+    assert got == tuple(want)
+    a = 0.05
+    b = rho * (bp + fp) / sum(want[0])
+    ref = oracle.schedule_transfers(*want, bp, fp, a, b)
+    slots, summary = cm.schedule_transfers(*got, bp, fp, a, b)
+    same_schedule(slots, summary, ref)
+    assert 0.0 < summary.utilization <= 1.0 and 0.0 <= summary.overlap <= 1.0 + 1e-12
+    plan.close()
+
+
+def test_schedule_argument_errors():
+    ok = dict(group_bytes=[1], ready=[0.0], need=[0.0], bp_len=1.0, fp_len=1.0, net_a=1.0, net_b=1.0)
+    cm.schedule_transfers(**ok)
+    for change in (dict(ready=[2.0]), dict(ready=[-0.5]), dict(need=[2.0]), dict(net_a=0.0, net_b=0.0),
+                   dict(net_a=-1.0), dict(bp_len=float("nan")), dict(ready=[float("nan")])):
+        with pytest.raises(cm.CaramelError) as ei:
+            cm.schedule_transfers(**{**ok, **change})
+        assert ei.value.status == binding.EINVAL
+    p = cm.Plan(2, [10, 10], batch_threshold_bytes=1024)
+    with pytest.raises(ValueError):
+        p.windows([0.0], [0.0, 1.0])
+    L = binding.lib()
+    assert L.caramel_plan_windows(p._h, None, None, None, None, None, 8) == binding.EINVAL
+    two = (binding.C.c_double * 2)(0.0, 1.0)
+    assert L.caramel_plan_windows(p._h, two, two, None, None, None, 0) == binding.EINVAL    # cap too small
+    assert L.caramel_plan_windows(p._h, two, two, None, None, None, 1) == binding.OK        # outputs optional
+    assert L.caramel_schedule_transfers(None, None, None, 1, 1.0, 1.0, 1.0, 1.0, None, None) == binding.EINVAL
+    assert L.caramel_schedule_transfers(None, None, None, 0, 1.0, 1.0, 1.0, 1.0, None, None) == binding.OK
