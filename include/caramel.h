@@ -229,12 +229,17 @@ int caramel_plan_serialize(const caramel_plan* plan, void* buf, size_t* len);
  *             at element w * fused_elems); may be NULL when fused_elems == 0, or when only
  *             caramel_allreduce in its default (direct) mode is going to be used.
  * The library uploads its descriptor tables (synchronously) and creates its internal stream.
- * May be called again to re-bind.  EINVAL: NULL/misaligned pointer.  EHIP: a HIP call failed. */
+ * May be called again to re-bind, with the same device current: the plan's tables, stream and
+ * events live on the device that is current at the first bind, and `stream` of the calls below
+ * must belong to it.  EINVAL: NULL/misaligned pointer, overlapping buffers (checked before any
+ * device call).  ESTATE: another device is current than at the first bind.  EHIP: a HIP call
+ * failed.  ENOMEM: out of host memory. */
 int caramel_bind(caramel_plan* plan, void* const* grads, void* fused_ws);
 
 /* `stream` is a hipStream_t handle (NULL = the default stream).  All four calls are
  * asynchronous: work is ordered after what is already queued on `stream`, and later work on
- * `stream` is ordered after it.  ESTATE: plan not bound (or no workspace where one is needed).
+ * `stream` is ordered after it.  ESTATE: plan not bound (or no workspace where one is needed),
+ * or another device is current than the one the plan was bound on.
  *
  * caramel_pack         batch units: every member tensor of every replica -> fused_ws at its
  *                      planned offset; alignment padding is written as +0.0 (section 4.2).

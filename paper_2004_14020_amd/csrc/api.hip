@@ -39,6 +39,18 @@ int fail(int code, const char* fmt, ...) {
     if (e_ != hipSuccess) return fail(CARAMEL_EHIP, "%s: %s", #expr, hipGetErrorString(e_)); \
   } while (0)
 
+// No exception leaves the library: allocation failures inside an entry point become ENOMEM.
+template <typename F>
+int guarded(F&& body) {
+  try {
+    return body();
+  } catch (const std::bad_alloc&) {
+    return fail(CARAMEL_ENOMEM, "out of host memory");
+  } catch (const std::exception& e) {
+    return fail(CARAMEL_ESTATE, "unexpected failure: %s", e.what());
+  }
+}
+
 struct Options {
   uint32_t launch_mode = CARAMEL_LAUNCH_AUTO;
   uint32_t batch_path = CARAMEL_BATCH_DIRECT;
@@ -79,6 +91,7 @@ struct caramel_plan {
   // device side (valid when bound)
   bool bound = false;
   bool has_ws = false;
+  int device = -1;  // the device that was current at bind: tables, stream and events live there
   TileTables tt;
   std::vector<LaunchGroup> groups[2];  // [0] staged tables, [1] direct tables
   bool groups_stale[2] = {true, true};
@@ -162,6 +175,7 @@ struct Timed {
     t.start = take_event(p);
     t.stop = take_event(p);
     if (!t.start || !t.stop) return;
+    p->pending.reserve(p->pending.size() + 4);  // the destructor must not have to allocate
     on = hipEventRecord(t.start, s) == hipSuccess;
   }
   ~Timed() {
@@ -332,6 +346,10 @@ int pipeline(caramel_plan* p, hipStream_t user, bool with_copies, bool direct) {
 int need_bound(const caramel_plan* p, bool needs_ws) {
   if (!p) return fail(CARAMEL_EINVAL, "plan is NULL");
   if (!p->bound) return fail(CARAMEL_ESTATE, "plan is not bound to device memory");
+  int dev = -1;
+  HIP_TRY(hipGetDevice(&dev));
+  if (dev != p->device)
+    return fail(CARAMEL_ESTATE, "plan was bound with device %d current, now device %d is", p->device, dev);
   if (needs_ws && p->host.fused_elems > 0 && !p->has_ws)
     return fail(CARAMEL_ESTATE, "this call needs the fused workspace, but none was bound");
   return CARAMEL_OK;
@@ -493,15 +511,17 @@ int caramel_plan_segments(const caramel_plan* p, uint32_t unit, uint64_t* seg_st
 
 int caramel_plan_serialize(const caramel_plan* p, void* buf, size_t* len) {
   if (!p || !len) return fail(CARAMEL_EINVAL, "NULL argument");
-  const std::vector<uint8_t> img = serialize(p->host);
-  if (!buf) {
+  return guarded([&]() -> int {
+    const std::vector<uint8_t> img = serialize(p->host);
+    if (!buf) {
+      *len = img.size();
+      return CARAMEL_OK;
+    }
+    if (*len < img.size()) return fail(CARAMEL_EINVAL, "buffer of %zu bytes, need %zu", *len, img.size());
+    std::memcpy(buf, img.data(), img.size());
     *len = img.size();
     return CARAMEL_OK;
-  }
-  if (*len < img.size()) return fail(CARAMEL_EINVAL, "buffer of %zu bytes, need %zu", *len, img.size());
-  std::memcpy(buf, img.data(), img.size());
-  *len = img.size();
-  return CARAMEL_OK;
+  });
 }
 
 int caramel_plan_set_option(caramel_plan* p, uint32_t option, uint64_t value) {
@@ -575,7 +595,18 @@ int caramel_plan_set_option(caramel_plan* p, uint32_t option, uint64_t value) {
   }
 }
 
+namespace {
+int bind_plan(caramel_plan* p, void* const* grads, void* fused_ws);
+}
+
 int caramel_bind(caramel_plan* p, void* const* grads, void* fused_ws) {
+  return guarded([&] { return bind_plan(p, grads, fused_ws); });
+}
+
+}  // extern "C"
+
+namespace {
+int bind_plan(caramel_plan* p, void* const* grads, void* fused_ws) {
   if (!p || !grads) return fail(CARAMEL_EINVAL, "NULL argument");
   const HostPlan& h = p->host;
   const uint32_t W = h.cfg.world;
@@ -603,9 +634,15 @@ int caramel_bind(caramel_plan* p, void* const* grads, void* fused_ws) {
   for (size_t i = 1; i < spans.size(); ++i)
     if (spans[i].lo < spans[i - 1].hi) return fail(CARAMEL_EINVAL, "gradient / workspace buffers overlap");
 
+  // a plan stays on the device it was first bound on: its stream and events live there
+  int dev = -1;
+  HIP_TRY(hipGetDevice(&dev));
+  if (p->device >= 0 && dev != p->device)
+    return fail(CARAMEL_ESTATE, "plan was bound with device %d current, now device %d is", p->device, dev);
   for (int s = 0; s < 2; ++s)
     if (p->streams[s]) HIP_TRY(hipStreamSynchronize(p->streams[s]));
   release_device(p);
+  p->device = dev;
 
   std::vector<uint64_t> rows((n + 1) * W, 0);
   for (uint32_t w = 0; w < W; ++w) {
@@ -631,31 +668,42 @@ int caramel_bind(caramel_plan* p, void* const* grads, void* fused_ws) {
   p->bound = true;
   return CARAMEL_OK;
 }
+}  // namespace
+
+extern "C" {
 
 int caramel_pack(caramel_plan* p, void* stream) {
-  if (int rc = need_bound(p, true)) return rc;
-  begin_call(p, hipStream_t(stream));
-  Range all{0, uint32_t(p->tt.copy.size())};
-  return run_copy(p, false, all, hipStream_t(stream));
+  return guarded([&]() -> int {
+    if (int rc = need_bound(p, true)) return rc;
+    begin_call(p, hipStream_t(stream));
+    Range all{0, uint32_t(p->tt.copy.size())};
+    return run_copy(p, false, all, hipStream_t(stream));
+  });
 }
 
 int caramel_unpack(caramel_plan* p, void* stream) {
-  if (int rc = need_bound(p, true)) return rc;
-  begin_call(p, hipStream_t(stream));
-  Range all{0, uint32_t(p->tt.copy.size())};
-  return run_copy(p, true, all, hipStream_t(stream));
+  return guarded([&]() -> int {
+    if (int rc = need_bound(p, true)) return rc;
+    begin_call(p, hipStream_t(stream));
+    Range all{0, uint32_t(p->tt.copy.size())};
+    return run_copy(p, true, all, hipStream_t(stream));
+  });
 }
 
 int caramel_ring_reduce(caramel_plan* p, void* stream) {
-  if (int rc = need_bound(p, true)) return rc;
-  // without a workspace there are no batch units, and the two tables coincide
-  return pipeline(p, hipStream_t(stream), false, !p->has_ws);
+  return guarded([&]() -> int {
+    if (int rc = need_bound(p, true)) return rc;
+    // without a workspace there are no batch units, and the two tables coincide
+    return pipeline(p, hipStream_t(stream), false, !p->has_ws);
+  });
 }
 
 int caramel_allreduce(caramel_plan* p, void* stream) {
-  const bool direct = p && (p->opt.batch_path == CARAMEL_BATCH_DIRECT || p->host.fused_elems == 0);
-  if (int rc = need_bound(p, !direct)) return rc;
-  return pipeline(p, hipStream_t(stream), true, direct);
+  return guarded([&]() -> int {
+    const bool direct = p && (p->opt.batch_path == CARAMEL_BATCH_DIRECT || p->host.fused_elems == 0);
+    if (int rc = need_bound(p, !direct)) return rc;
+    return pipeline(p, hipStream_t(stream), true, direct);
+  });
 }
 
 int caramel_profile(caramel_plan* p, int enable) {
@@ -668,7 +716,18 @@ int caramel_profile(caramel_plan* p, int enable) {
   return CARAMEL_OK;
 }
 
+namespace {
+int read_profile(caramel_plan* p, caramel_kernel_stat* out);
+}
+
 int caramel_profile_read(caramel_plan* p, caramel_kernel_stat* out) {
+  return guarded([&] { return read_profile(p, out); });
+}
+
+}  // extern "C"
+
+namespace {
+int read_profile(caramel_plan* p, caramel_kernel_stat* out) {
   if (int rc = need_bound(p, false)) return rc;
   if (!out) return fail(CARAMEL_EINVAL, "out is NULL");
   // every pending stop event has completed once its own synchronize returns
@@ -713,6 +772,9 @@ int caramel_profile_read(caramel_plan* p, caramel_kernel_stat* out) {
   std::memcpy(out, p->stats, sizeof p->stats);
   return CARAMEL_OK;
 }
+}  // namespace
+
+extern "C" {
 
 const char* caramel_last_error(void) { return g_err.c_str(); }
 
