@@ -38,6 +38,7 @@ def parse_args():
     ap.add_argument("--block", type=int, default=None)
     ap.add_argument("--pattern", choices=["ring", "hd", "shuffle"], default="ring")
     ap.add_argument("--launch-min-bytes", type=int, default=None)
+    ap.add_argument("--align-tiles", type=int, default=None, help="0..3, see CARAMEL_OPT_ALIGN_TILES")
     ap.add_argument("--device-fill", action="store_true",
                     help="fill the replicas on the device instead of uploading Philox samples")
     ap.add_argument("--no-cpu-baseline", action="store_true")
@@ -98,7 +99,8 @@ def main() -> int:
         plan.set_option(cm.OPT_BATCH_PATH, cm.BATCH_STAGED if staged else cm.BATCH_DIRECT)
     for opt, val in ((cm.OPT_TILE_VECS, args.tile_vecs), (cm.OPT_MAX_GRID, args.max_grid),
                      (cm.OPT_NONTEMPORAL, args.nontemporal), (cm.OPT_UNROLL, args.unroll),
-                     (cm.OPT_BLOCK, args.block), (cm.OPT_LAUNCH_MIN_BYTES, args.launch_min_bytes)):
+                     (cm.OPT_BLOCK, args.block), (cm.OPT_LAUNCH_MIN_BYTES, args.launch_min_bytes),
+                     (cm.OPT_ALIGN_TILES, args.align_tiles)):
         if val is not None:
             plan.set_option(opt, val)
 

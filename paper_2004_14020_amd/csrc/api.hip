@@ -560,6 +560,10 @@ int caramel_plan_set_option(caramel_plan* p, uint32_t option, uint64_t value) {
       if (value < 64 || value > (1u << 20)) return fail(CARAMEL_EINVAL, "tile_vecs must be in [64, 2^20]");
       p->opt.shape.medium_vecs = uint32_t(value);
       return CARAMEL_OK;
+    case CARAMEL_OPT_ALIGN_TILES:
+      if (value > 3) return fail(CARAMEL_EINVAL, "align_tiles must be 0..3");
+      p->opt.shape.align_tiles = uint32_t(value);
+      return CARAMEL_OK;
     case CARAMEL_OPT_LONG_LAUNCH_BYTES:
       p->opt.shape.long_bytes = value;
       return CARAMEL_OK;

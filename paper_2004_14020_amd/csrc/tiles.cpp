@@ -5,15 +5,18 @@
 namespace caramel {
 namespace {
 
-// Cut the element run [a, b) of a row (run starts at element `row_elem0 + a`) into tiles.
+// Cut the run of `n` elements that starts at element `row_elem` of a row into tiles.  `phase` is
+// the byte address of the run's start modulo the tile size (0 if unknown): the first tile is
+// shortened so that every later tile starts on a multiple of the tile size in memory.
 void cut_run(std::vector<ReduceTile>& out, uint32_t row, uint32_t first, uint64_t row_elem, uint64_t n,
-             uint64_t vec_elems, uint64_t tile_elems) {
-  for (uint64_t at = 0; at < n; at += tile_elems) {
+             uint64_t vec_elems, uint64_t tile_elems, uint64_t phase_elems) {
+  uint64_t len = phase_elems ? tile_elems - phase_elems : tile_elems;
+  for (uint64_t at = 0; at < n; at += len, len = tile_elems) {
     ReduceTile t;
     t.row = row;
     t.first = first;
     t.vec_off = uint32_t((row_elem + at) / vec_elems);
-    t.n_elems = uint32_t(std::min(tile_elems, n - at));
+    t.n_elems = uint32_t(std::min(len, n - at));
     out.push_back(t);
   }
 }
@@ -48,6 +51,17 @@ void build_tiles(const HostPlan& p, const TileShape& ts, TileTables& out, const 
   for (int s = 0; s < 2; ++s)
     out.long_launches[s] = large_total[s] >= ts.long_bytes && large_total[s] > 0 && aligned[s];
 
+  // Position of a row's element inside an aligned tile-sized block of memory, in elements, if it
+  // is the same in every replica (else, or without addresses, 0: tiles start where the run starts).
+  auto phase = [&](uint32_t row, uint64_t elem, uint64_t tile_elems, int cls) -> uint64_t {
+    if (!row_addr || !(ts.align_tiles & (cls == kSmall ? 1u : 2u))) return 0;
+    const uint64_t tile_b = tile_elems * p.elem_size();
+    const uint64_t ph = (row_addr[size_t(row) * W] + elem * p.elem_size()) % tile_b;
+    for (uint32_t w = 1; w < W; ++w)
+      if ((row_addr[size_t(row) * W + w] + elem * p.elem_size()) % tile_b != ph) return 0;
+    return ph / p.elem_size();
+  };
+
   for (int cls = 0; cls < 2; ++cls)
     for (uint32_t s = 0; s < p.cfg.num_streams; ++s)
       for (uint32_t ui : out.order[cls][s]) {
@@ -67,16 +81,19 @@ void build_tiles(const HostPlan& p, const TileShape& ts, TileTables& out, const 
           // order that does not depend on the segment and read the workers from 0
           const uint32_t first = p.cfg.pattern == CARAMEL_PATTERN_RING ? (c + 1) % W : 0;
           if (u.kind == CARAMEL_KIND_CHUNK) {
-            cut_run(out.staged, ent[0].tensor, first, ent[0].tensor_off + a, b - a, ve, tile_elems);
-            cut_run(out.direct, ent[0].tensor, first, ent[0].tensor_off + a, b - a, ve, tile_elems);
+            const uint64_t ph = phase(ent[0].tensor, ent[0].tensor_off + a, tile_elems, cls);
+            cut_run(out.staged, ent[0].tensor, first, ent[0].tensor_off + a, b - a, ve, tile_elems, ph);
+            cut_run(out.direct, ent[0].tensor, first, ent[0].tensor_off + a, b - a, ve, tile_elems, ph);
             continue;
           }
-          cut_run(out.staged, fused_row, first, u.fused_off + a, b - a, ve, tile_elems);
+          cut_run(out.staged, fused_row, first, u.fused_off + a, b - a, ve, tile_elems,
+                  phase(fused_row, u.fused_off + a, tile_elems, cls));
           for (uint32_t k = 0; k < u.n_entries; ++k) {
             const caramel_entry& e = ent[k];
             const uint64_t lo = std::max(a, e.unit_off), hi = std::min(b, e.unit_off + e.elems);
             if (lo >= hi) continue;
-            cut_run(out.direct, e.tensor, first, e.tensor_off + (lo - e.unit_off), hi - lo, ve, tile_elems);
+            const uint64_t te = e.tensor_off + (lo - e.unit_off);
+            cut_run(out.direct, e.tensor, first, te, hi - lo, ve, tile_elems, phase(e.tensor, te, tile_elems, cls));
           }
         }
 

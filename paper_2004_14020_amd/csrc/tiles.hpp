@@ -40,6 +40,7 @@ struct TileShape {
   uint64_t large_bytes = 4u << 20;   // a chunk unit of at least this many bytes per replica is "large"
   uint64_t long_bytes = 64u << 20;   // a stream whose large units total at least this much gets long launches
   uint32_t copy_vecs = 512;          // vectors per copy tile
+  uint32_t align_tiles = 1;          // bit 0: small tiles, bit 1: medium tiles start on multiples of their size in memory where possible
 };
 
 // A unit whose tiles have the large shape: long uniform runs, worth 1024-lane workgroups.

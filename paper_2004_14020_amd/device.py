@@ -23,11 +23,13 @@ class Replicas:
     Tensor t of every replica starts at the same offset in its arena, like the flat gradient
     buffer of a training framework.  Tensors of at least `large_bytes` start on `large_align`
     boundaries (64 KiB: the reduce kernel's large tiles then coincide with aligned 64 KiB
-    blocks of memory, which it streams measurably faster); the others on `slot_align`."""
+    blocks of memory, which it streams measurably faster); the others on `slot_align`.
+    `arena_phase`, if given, makes every arena start at an address congruent to it modulo
+    64 KiB (a multiple of 256), so that tests can choose how runs sit relative to aligned blocks."""
 
     def __init__(self, plan: Plan, elems: Sequence[int], device: str = "cuda:0", slot_align: int = 256,
                  large_align: int = 65536, large_bytes: int = 1 << 20,
-                 with_workspace: bool = True):
+                 with_workspace: bool = True, arena_phase: Optional[int] = None):
         self.plan = plan
         self.world = plan.cfg.world
         self.elems = [int(e) for e in elems]
@@ -42,8 +44,18 @@ class Replicas:
             at += n * self.es
         self.offsets = offs
         self.arena_bytes = max(at, slot_align)
-        self.arenas = [torch.empty(self.arena_bytes, dtype=torch.uint8, device=self.device)
-                       for _ in range(self.world)]
+        if arena_phase is None:
+            self.arenas = [torch.empty(self.arena_bytes, dtype=torch.uint8, device=self.device)
+                           for _ in range(self.world)]
+        else:
+            if arena_phase % 256 or not 0 <= arena_phase < 65536:
+                raise ValueError("arena_phase must be a multiple of 256 below 65536")
+            self._backing = [torch.empty(self.arena_bytes + 2 * 65536, dtype=torch.uint8, device=self.device)
+                             for _ in range(self.world)]
+            self.arenas = []
+            for b in self._backing:
+                skip = (arena_phase - b.data_ptr()) % 65536
+                self.arenas.append(b[skip:skip + self.arena_bytes])
         fe = plan.fused_elems
         self.fused: Optional[torch.Tensor] = None
         if with_workspace and fe > 0:

@@ -27,7 +27,7 @@ static int fails = 0;
   } while (0)
 
 static void check_case(const caramel_config& cfg, const std::vector<uint64_t>& elems, uint32_t tile_vecs,
-                       uint32_t small_vecs, uint64_t large_bytes, uint32_t copy_vecs) {
+                       uint32_t small_vecs, uint64_t large_bytes, uint32_t copy_vecs, uint64_t addr_seed) {
   HostPlan p;
   std::string why;
   const int rc = build_host_plan(cfg, elems.data(), uint32_t(elems.size()), nullptr, 0.0, 0.0, p, why);
@@ -41,9 +41,24 @@ static void check_case(const caramel_config& cfg, const std::vector<uint64_t>& e
   shape.long_bytes = (large_bytes % 3 == 0) ? 0 : 200000;
   shape.medium_vecs = 128;
   shape.copy_vecs = copy_vecs;
-  build_tiles(p, shape, tt);
+  shape.align_tiles = uint32_t(addr_seed >> 8) & 3u;
+  // addr_seed 0: no addresses (tiles start where runs start).  Otherwise made-up base addresses,
+  // aligned as bind demands; odd seeds give every replica the same position inside a tile-sized
+  // block (tiles must then start on multiples of the tile size), even seeds different ones.
   const uint64_t es = p.elem_size(), ve = 16 / es, W = cfg.world;
   const uint32_t fused_row = uint32_t(elems.size());
+  std::vector<uint64_t> addr;
+  if (addr_seed) {
+    std::mt19937_64 ar(addr_seed);
+    addr.resize((elems.size() + 1) * W);
+    for (size_t row = 0; row <= elems.size(); ++row) {
+      const uint64_t common = (ar() % 4096) * cfg.align_bytes;
+      for (uint64_t w = 0; w < W; ++w)
+        addr[row * W + w] = (uint64_t(1) << 40) * (w + 1) + (uint64_t(row) << 32) +
+                            ((addr_seed & 1) ? common : (ar() % 4096) * cfg.align_bytes);
+    }
+  }
+  build_tiles(p, shape, tt, addr_seed ? addr.data() : nullptr);
   auto row_elems = [&](uint32_t row) { return row == fused_row ? p.fused_elems : elems[row]; };
 
   for (int table = 0; table < 2; ++table) {
@@ -58,6 +73,8 @@ static void check_case(const caramel_config& cfg, const std::vector<uint64_t>& e
       const Range r = per_unit[u];
       CHECK(uint64_t(r.begin) + r.count <= tiles.size());
       total_tiles += r.count;
+      uint32_t prev_row = ~0u, prev_seg = ~0u;
+      uint64_t prev_end = ~0ull;
       for (uint32_t i = r.begin; i < r.begin + r.count; ++i) {
         const ReduceTile& t = tiles[i];
         CHECK(t.n_elems > 0 && t.n_elems <= uint64_t(!is_large_unit(p, u, shape) ? small_vecs : (tt.long_launches[un.stream] ? tile_vecs : shape.medium_vecs)) * ve);
@@ -93,6 +110,15 @@ static void check_case(const caramel_config& cfg, const std::vector<uint64_t>& e
         while (c + 1 < W && seg[c + 1] <= unit_pos) ++c;
         CHECK(unit_pos >= seg[c] && unit_pos + t.n_elems <= seg[c + 1]);
         CHECK(t.first == (cfg.pattern == CARAMEL_PATTERN_RING ? (c + 1) % W : 0));
+        if ((addr_seed & 1) && (shape.align_tiles & (is_large_unit(p, u, shape) ? 2u : 1u))) {
+          // same phase in every replica: a tile that does not begin its run begins an aligned block
+          const uint64_t cap_b = uint64_t(!is_large_unit(p, u, shape) ? small_vecs : (tt.long_launches[un.stream] ? tile_vecs : shape.medium_vecs)) * 16;
+          const bool continues = i > r.begin && prev_row == t.row && prev_end == e0 && prev_seg == c;
+          if (continues) CHECK((addr[size_t(t.row) * W] + e0 * es) % cap_b == 0);
+        }
+        prev_row = t.row;
+        prev_end = e1;
+        prev_seg = c;
         std::vector<uint8_t>& s = seen[t.row];
         if (s.empty()) s.assign(row_elems(t.row), 0);
         for (uint64_t e = e0; e < e1; ++e) {
@@ -209,7 +235,7 @@ int main() {
     std::vector<uint64_t> elems(1 + rng() % 14);
     for (uint64_t& e : elems) e = pick({1, 2, 3, 5, 8, 17, 64, 100, 255, 256, 257, 1000, 4096, 5000, 70000});
     check_case(cfg, elems, uint32_t(pick({64, 256, 1024, 4096})), uint32_t(pick({64, 256, 1024})),
-               pick({0, 1024, 65536, 1u << 22}), uint32_t(pick({64, 512})));
+               pick({0, 1024, 65536, 1u << 22}), uint32_t(pick({64, 512})), it % 3 == 0 ? 0 : rng());
   }
   // rejected configurations must not crash
   HostPlan p;

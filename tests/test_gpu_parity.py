@@ -123,6 +123,25 @@ def test_alignment_and_split_modes(align, mode, S):
         plan.close()
 
 
+@pytest.mark.parametrize("phase", [0, 256, 1280, 4096 - 256, 65536 - 512])
+@pytest.mark.parametrize("align_tiles", [0, 1, 2, 3])
+def test_tiles_cut_on_aligned_blocks_give_the_same_bits(phase, align_tiles):
+    """Every replica at the same position inside an aligned block: small tiles (bit 0) and medium
+    tiles (bit 1) are then cut on multiples of their size in memory, with a short first tile."""
+    print(f"case: aligned tiles phase={phase} align_tiles={align_tiles}", flush=True)
+    cfg = small_cfg(8, oracle.F32)
+    elems = list(SMALL_ELEMS)
+    grads = make_inputs(cfg, elems, seed=11)
+    ref = oracle_result(cfg, elems, grads)
+    for extra in ({}, {cm.OPT_LARGE_UNIT_BYTES: 65536, cm.OPT_MEDIUM_TILE_VECS: 256, cm.OPT_BATCH_PATH: cm.BATCH_STAGED}):
+        plan = lib_plan(cfg, elems, {cm.OPT_ALIGN_TILES: align_tiles, cm.OPT_SMALL_TILE_VECS: 64, **extra})
+        dev = Replicas(plan, elems, slot_align=256, large_align=256, arena_phase=phase)
+        dev.upload(grads)
+        plan.allreduce()
+        assert_same_bits(dev.download(), ref, f"phase {phase}, align_tiles {align_tiles}, {extra}")
+        plan.close()
+
+
 def test_batching_off_and_single_tiny_tensor():
     for elems, T in (([1], 0), ([3, 5], 0), ([2], 1 << 20), ([5, 3, 9], 1 << 20)):
         for W in (1, 4, 16):
