@@ -11,6 +11,8 @@
 //                  one wavefront per run.
 #include "kernels.hpp"
 
+#include <type_traits>
+
 namespace caramel {
 namespace {
 
@@ -280,8 +282,10 @@ k_ring_reduce_sm(const ReduceTile* __restrict__ tiles, const uint64_t* __restric
   }
 }
 
-// Any W: pointers are fetched as the chain advances.
-template <bool BF16, bool NT>
+// Any W: the chain is walked one worker at a time, like the stream-major kernel: the next
+// worker's base pointer (a scalar load) and its U vectors per lane are requested while the
+// current ones are added.
+template <bool BF16, bool NT, int U>
 __global__ void __launch_bounds__(kMaxBlock)
 k_ring_reduce_any(const ReduceTile* __restrict__ tiles, const uint64_t* __restrict__ rows, uint32_t begin,
                   uint32_t count, uint32_t W, float inv_w) {
@@ -290,17 +294,46 @@ k_ring_reduce_any(const ReduceTile* __restrict__ tiles, const uint64_t* __restri
     const ReduceTile tl = tiles[begin + ti];
     const uint64_t* row = rows + size_t(tl.row) * W;
     const uint32_t nvec = tl.n_elems / VE;
-    for (uint32_t v = threadIdx.x; v < nvec; v += blockDim.x) {
+    const uint32_t B = blockDim.x;
+    // one pass of the chain over N vectors of this lane, B apart, starting at v
+    auto chain = [&](uint32_t v, auto n_tag) {
+      constexpr int N = decltype(n_tag)::value;
+      Chain<BF16> acc[N];
+      u32x4 cur[N], nxt[N];
       uint32_t w = tl.first;
-      Chain<BF16> c;
-      c.start(ld<NT>(reinterpret_cast<gvec_ptr>(row[w]) + tl.vec_off + v));
+      gvec_ptr base = reinterpret_cast<gvec_ptr>(row[w]) + tl.vec_off;
+#pragma unroll
+      for (int u = 0; u < N; ++u) cur[u] = ld<NT>(at(base, (v + u * B) * 16u));
       for (uint32_t k = 1; k < W; ++k) {
         w = (w + 1 == W) ? 0 : w + 1;
-        c.add(ld<NT>(reinterpret_cast<gvec_ptr>(row[w]) + tl.vec_off + v));
+        base = reinterpret_cast<gvec_ptr>(row[w]) + tl.vec_off;
+#pragma unroll
+        for (int u = 0; u < N; ++u) nxt[u] = ld<NT>(at(base, (v + u * B) * 16u));
+        __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+        for (int u = 0; u < N; ++u) {
+          if (k == 1) acc[u].start(cur[u]);
+          else acc[u].add(cur[u]);
+          cur[u] = nxt[u];
+        }
+        __builtin_amdgcn_sched_barrier(0);
       }
-      const u32x4 y = c.finish(inv_w);
-      for (uint32_t k = 0; k < W; ++k) st<NT>(reinterpret_cast<gvec_ptr>(row[k]) + tl.vec_off + v, y);
-    }
+      u32x4 y[N];
+#pragma unroll
+      for (int u = 0; u < N; ++u) {
+        if (W == 1) acc[u].start(cur[u]);
+        else acc[u].add(cur[u]);
+        y[u] = acc[u].finish(inv_w);
+      }
+      for (uint32_t k = 0; k < W; ++k) {
+        base = reinterpret_cast<gvec_ptr>(row[k]) + tl.vec_off;
+#pragma unroll
+        for (int u = 0; u < N; ++u) st<NT>(at(base, (v + u * B) * 16u), y[u]);
+      }
+    };
+    uint32_t v = threadIdx.x;
+    for (; v + (U - 1) * B < nvec; v += U * B) chain(v, std::integral_constant<int, U>{});
+    for (; v < nvec; v += B) chain(v, std::integral_constant<int, 1>{});
     const uint32_t rem = tl.n_elems - nvec * VE;
     if (threadIdx.x < rem) {
       const size_t e = size_t(tl.vec_off) * VE + nvec * VE + threadIdx.x;
@@ -422,7 +455,7 @@ hipError_t launch_ring_reduce(const ReduceArgs& a, hipStream_t s) {
   // the loop kernel adds as a chain; a tree over one worker is the same thing
   if (a.tree && a.world != 1) return hipErrorInvalidValue;
 #define CARAMEL_ANY(BF, NT) \
-  hipLaunchKernelGGL((k_ring_reduce_any<BF, NT>), grid, dim3(a.block), 0, s, a.tiles, a.rows, a.begin, a.count, a.world, inv_w)
+  hipLaunchKernelGGL((k_ring_reduce_any<BF, NT, 4>), grid, dim3(a.block), 0, s, a.tiles, a.rows, a.begin, a.count, a.world, inv_w)
   if (a.bf16) {
     if (a.nontemporal) CARAMEL_ANY(true, true); else CARAMEL_ANY(true, false);
   } else {
