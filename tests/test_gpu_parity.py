@@ -277,6 +277,47 @@ def test_other_patterns_match_the_oracle(pattern, W, dtype):
         plan.close()
 
 
+@pytest.mark.parametrize("W", [6, 12, 24, 64])
+@pytest.mark.parametrize("dtype", [oracle.F32, oracle.BF16])
+def test_world_sizes_of_the_generic_kernel_including_the_maximum(W, dtype):
+    """World sizes without a specialised kernel, up to CARAMEL_MAX_WORLD, with large tiles too."""
+    print(f"case: generic W={W} dtype={dtype}", flush=True)
+    cfg = small_cfg(W, dtype)
+    elems = list(SMALL_ELEMS)
+    grads = make_inputs(cfg, elems, seed=60 + W)
+    ref = oracle_result(cfg, elems, grads)
+    for opts in ({}, {cm.OPT_LARGE_UNIT_BYTES: 0, cm.OPT_LONG_LAUNCH_BYTES: 0, cm.OPT_TILE_VECS: 4096}):
+        plan = lib_plan(cfg, elems, opts)
+        dev = Replicas(plan, elems)
+        dev.upload(grads)
+        plan.allreduce()
+        assert_same_bits(dev.download(), ref, f"W {W} options {opts}")
+        plan.close()
+
+
+def test_two_plans_on_two_streams_at_once():
+    """Two independent plans queued on two caller streams with no synchronisation between them:
+    each has its own tables, internal stream and events, so both results must be exact."""
+    import torch
+    print("case: two plans at once", flush=True)
+    cases = []
+    for i, (W, dtype) in enumerate(((8, oracle.F32), (4, oracle.BF16))):
+        cfg = small_cfg(W, dtype)
+        elems = list(SMALL_ELEMS) + [300000 + i]
+        grads = make_inputs(cfg, elems, seed=70 + i)
+        plan = lib_plan(cfg, elems, {cm.OPT_PIPELINE_MIN_BYTES: 0})
+        dev = Replicas(plan, elems)
+        dev.upload(grads)
+        cases.append((cfg, elems, grads, plan, dev, torch.cuda.Stream()))
+    torch.cuda.synchronize()
+    for _, _, _, plan, _, stream in cases:
+        plan.allreduce(stream.cuda_stream)
+    torch.cuda.synchronize()
+    for cfg, elems, grads, plan, dev, _ in cases:
+        assert_same_bits(dev.download(), oracle_result(cfg, elems, grads), f"plan with W {cfg.world}")
+        plan.close()
+
+
 @pytest.mark.parametrize("W", [3, 5, 33])
 def test_shuffle_with_any_world_size(W):
     cfg = oracle.Config(W, oracle.F32, 8192, oracle.SPLIT_FIXED, 8, 65536, 16, 2, oracle.PATTERN_SHUFFLE)
