@@ -30,9 +30,9 @@ What is computed (all integer work, hence compared bit-exactly):
 * Threshold choice (section 4.2): with transfer time f(d) fitted as a + b*d from
   two measurements, the threshold is the smallest size x with f(2x) / (2 f(x)) > 0.8.
 
-Readings of points the paper leaves open (equality with the threshold counts as
+Readings of points the paper leaves open: equality with the threshold counts as
 large; a large parameter does not flush the open batch; members of a batch
-start on granule boundaries) are the ones listed in the design notes.
+start on granule boundaries.
 """
 from __future__ import annotations
 
