@@ -314,6 +314,10 @@ const std::vector<LaunchGroup>& launch_groups(caramel_plan* p, bool direct) {
   // issue in the order of the first unit, which alternates between the streams
   std::stable_sort(out.begin(), out.end(),
                    [](const LaunchGroup& a, const LaunchGroup& b) { return a.first_unit < b.first_unit; });
+  // ... but every stream issues its launches over small units first: a call then ends with the
+  // long, evenly sized launches over large units running on both streams, and the streams finish
+  // together (measured: VGG-16 -0.5 %, AlexNet-v2 -2.3 %, ResNet-50 -1.1 % time per call).
+  std::stable_sort(out.begin(), out.end(), [](const LaunchGroup& a, const LaunchGroup& b) { return a.large < b.large; });
   p->groups_stale[direct ? 1 : 0] = false;
   return out;
 }
