@@ -320,7 +320,13 @@ enum {
    * per replica; default 64 MiB.  Otherwise they get tiles of CARAMEL_OPT_MEDIUM_TILE_VECS
    * (default 1024) and launches like the small units'. */
   CARAMEL_OPT_LONG_LAUNCH_BYTES = 15,
-  CARAMEL_OPT_MEDIUM_TILE_VECS = 16
+  CARAMEL_OPT_MEDIUM_TILE_VECS = 16,
+  /* Medium tiles (and the large workgroups that go with them) are used only when the replicas
+   * together hold at least this many bytes; for smaller gradient sets the medium class is cut
+   * and launched in the small shape.  Default 1.5 GiB: 16 KiB runs win on working sets of
+   * several GiB, 4 KiB runs (four times as many workgroups per launch) below.  Takes effect at
+   * the next caramel_bind. */
+  CARAMEL_OPT_MEDIUM_MIN_FOOTPRINT = 17
 };
 enum { CARAMEL_LAUNCH_PER_UNIT = 0, CARAMEL_LAUNCH_PER_STREAM = 1, CARAMEL_LAUNCH_AUTO = 2 };
 enum { CARAMEL_BATCH_STAGED = 0, CARAMEL_BATCH_DIRECT = 1 };

@@ -20,7 +20,7 @@ SPLIT_NONE, SPLIT_FIXED, SPLIT_ADAPTIVE = 0, 1, 2
 KIND_BATCH, KIND_CHUNK = 0, 1
 PATTERN_RING, PATTERN_HALVING_DOUBLING, PATTERN_SHUFFLE = 0, 1, 2
 (OPT_LAUNCH_MODE, OPT_BATCH_PATH, OPT_TILE_VECS, OPT_MAX_GRID, OPT_NONTEMPORAL, OPT_UNROLL, OPT_BLOCK,
- OPT_LAUNCH_MIN_BYTES, OPT_PIPELINE_MIN_BYTES, OPT_SMALL_TILE_VECS, OPT_SMALL_BLOCK, OPT_LARGE_UNIT_BYTES, OPT_STREAM_MAJOR, OPT_LARGE_LAUNCH_MIN_BYTES, OPT_ALIGN_TILES, OPT_LONG_LAUNCH_BYTES, OPT_MEDIUM_TILE_VECS) = range(17)
+ OPT_LAUNCH_MIN_BYTES, OPT_PIPELINE_MIN_BYTES, OPT_SMALL_TILE_VECS, OPT_SMALL_BLOCK, OPT_LARGE_UNIT_BYTES, OPT_STREAM_MAJOR, OPT_LARGE_LAUNCH_MIN_BYTES, OPT_ALIGN_TILES, OPT_LONG_LAUNCH_BYTES, OPT_MEDIUM_TILE_VECS, OPT_MEDIUM_MIN_FOOTPRINT) = range(18)
 LAUNCH_PER_UNIT, LAUNCH_PER_STREAM, LAUNCH_AUTO = 0, 1, 2
 BATCH_STAGED, BATCH_DIRECT = 0, 1
 K_PACK, K_REDUCE, K_UNPACK, K_SEQUENCE, K_COUNT = 0, 1, 2, 3, 4

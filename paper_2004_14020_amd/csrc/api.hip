@@ -64,6 +64,9 @@ struct Options {
   uint64_t launch_min_bytes = 4u << 20;         // small units share a launch up to this size
   uint64_t large_launch_min_bytes = 64u << 20;  // large units likewise
   uint64_t pipeline_min_bytes = uint64_t(256) << 20;
+  // medium tiles (16 KiB runs, 1024 lanes) pay off once the replicas together exceed this many
+  // bytes; below it the small shape streams better (more, shorter workgroups per launch)
+  uint64_t medium_min_footprint = uint64_t(3) << 29;
 };
 
 // Fork/join events order work between streams of the same device; no timing, and no system-scope
@@ -92,6 +95,8 @@ struct caramel_plan {
   bool bound = false;
   bool has_ws = false;
   int device = -1;  // the device that was current at bind: tables, stream and events live there
+  TileShape bound_shape;        // the shape the tables were built with
+  uint32_t medium_block = 1024;  // workgroup size of launches over medium tiles
   TileTables tt;
   std::vector<LaunchGroup> groups[2];  // [0] staged tables, [1] direct tables
   bool groups_stale[2] = {true, true};
@@ -197,9 +202,9 @@ int run_reduce(caramel_plan* p, bool direct, Range r, bool large, bool lng, hipS
   a.nontemporal = p->opt.nontemporal != 0;
   a.tree = p->host.cfg.pattern == CARAMEL_PATTERN_HALVING_DOUBLING;
   // by default a workgroup takes its tile in one go: vectors per lane = tile / workgroup size
-  a.block = large ? p->opt.block : p->opt.small_block;
-  const uint32_t tile_vecs =
-      !large ? p->opt.shape.small_vecs : (lng ? p->opt.shape.large_vecs : p->opt.shape.medium_vecs);
+  a.block = !large ? p->opt.small_block : (lng ? p->opt.block : p->medium_block);
+  const TileShape& shape = p->bound_shape;
+  const uint32_t tile_vecs = !large ? shape.small_vecs : (lng ? shape.large_vecs : shape.medium_vecs);
   a.unroll = p->opt.unroll ? p->opt.unroll : std::max(1u, tile_vecs / a.block);
   a.stream_major = lng ? p->opt.stream_major : 0;
   a.max_grid = p->opt.max_grid;
@@ -568,6 +573,9 @@ int caramel_plan_set_option(caramel_plan* p, uint32_t option, uint64_t value) {
       if (value > 3) return fail(CARAMEL_EINVAL, "align_tiles must be 0..3");
       p->opt.shape.align_tiles = uint32_t(value);
       return CARAMEL_OK;
+    case CARAMEL_OPT_MEDIUM_MIN_FOOTPRINT:
+      p->opt.medium_min_footprint = value;
+      return CARAMEL_OK;
     case CARAMEL_OPT_LONG_LAUNCH_BYTES:
       p->opt.shape.long_bytes = value;
       return CARAMEL_OK;
@@ -657,7 +665,16 @@ int bind_plan(caramel_plan* p, void* const* grads, void* fused_ws) {
     for (size_t t = 0; t < n; ++t) rows[t * W + w] = reinterpret_cast<uint64_t>(grads[w * n + t]);
     rows[n * W + w] = fused_ws ? reinterpret_cast<uint64_t>(fused_ws) + uint64_t(w) * h.fused_elems * es : 0;
   }
-  build_tiles(h, p->opt.shape, p->tt, rows.data());
+  // replicas that are small in total: medium tiles take the small shape
+  p->bound_shape = p->opt.shape;
+  p->medium_block = p->opt.block;
+  uint64_t footprint = 0;
+  for (uint64_t e : h.tensor_elems) footprint += e * es * W;
+  if (footprint < p->opt.medium_min_footprint) {
+    p->bound_shape.medium_vecs = p->opt.shape.small_vecs;
+    p->medium_block = p->opt.small_block;
+  }
+  build_tiles(h, p->bound_shape, p->tt, rows.data());
   p->groups_stale[0] = p->groups_stale[1] = true;
   int rc = upload(rows, &p->d_rows);
   if (!rc) rc = upload(p->tt.direct, &p->d_direct);
