@@ -287,12 +287,13 @@ const std::vector<LaunchGroup>& launch_groups(caramel_plan* p, bool direct) {
   for (int cls = 0; cls < 2; ++cls) {
     for (uint32_t lane = 0; lane < lanes; ++lane) {
       LaunchGroup g{};
-      uint64_t bytes = 0;
+      uint64_t bytes = 0, min_bytes = 0;
       bool open = false;
+      const size_t mine = out.size();  // launches of this class and lane start here
       for (uint32_t s = 0; s < p->host.cfg.num_streams; ++s) {
         if (pipelined && s != lane) continue;
         const bool lng = cls == kLarge && tt.long_launches[s];
-        const uint64_t min_bytes = lng ? p->opt.large_launch_min_bytes : p->opt.launch_min_bytes;
+        min_bytes = lng ? p->opt.large_launch_min_bytes : p->opt.launch_min_bytes;
         // tiles of a long-launch stream and of another stream differ in shape: never one launch
         if (open && g.lng != lng) {
           out.push_back(g);
@@ -313,7 +314,19 @@ const std::vector<LaunchGroup>& launch_groups(caramel_plan* p, bool direct) {
           }
         }
       }
-      if (open) out.push_back(g);
+      if (open) {
+        // what is left over at the end is rarely worth a launch of its own: less than half the
+        // minimum joins the launch before it (its tiles follow that launch's in the table)
+        LaunchGroup* prev = out.size() > mine ? &out.back() : nullptr;
+        if (prev && bytes < min_bytes / 2 && prev->lng == g.lng &&
+            prev->reduce.begin + prev->reduce.count == g.reduce.begin &&
+            prev->copy.begin + prev->copy.count == g.copy.begin) {
+          prev->reduce.count += g.reduce.count;
+          prev->copy.count += g.copy.count;
+        } else {
+          out.push_back(g);
+        }
+      }
     }
   }
   // issue in the order of the first unit, which alternates between the streams
