@@ -185,6 +185,15 @@ def test_windows_of_a_batch_come_from_its_last_updated_and_first_read_member():
     assert nbytes == [256 * 4, 4096 * 4] and ready == [3.0, 4.0] and need == [7.0, 6.0]
 
 
+def test_chunks_of_a_split_tensor_share_its_boundaries():
+    from oracle import SPLIT_FIXED
+    plan = build_plan(Config(2, F32, 1024, SPLIT_FIXED, 8, 4096), [3000, 16])     # 12000 B -> chunks of 4096 B
+    assert [u.elems for u in plan.units] == [1024, 1024, 952, 16]
+    nbytes, ready, need = group_windows(plan, [2.5, 3.5], [8.0, 1.0])
+    assert nbytes == [4096, 4096, 3808, 64]
+    assert ready == [2.5, 2.5, 2.5, 3.5] and need == [8.0, 8.0, 8.0, 1.0]
+
+
 def test_argument_errors():
     with pytest.raises(ValueError):
         schedule_transfers([1], [0.0], [0.0, 1.0], 1.0, 1.0, 1.0, 1.0)
