@@ -155,8 +155,8 @@ def validate(cfg: Config, elems: Sequence[int]) -> None:
         raise ValueError("max_depth")
     if cfg.pattern not in (PATTERN_RING, PATTERN_HALVING_DOUBLING, PATTERN_SHUFFLE):
         raise ValueError("pattern")
-    if cfg.pattern == PATTERN_HALVING_DOUBLING and cfg.world not in (1, 2, 4, 8, 16):
-        raise ValueError("halving-doubling needs a power-of-two world of at most 16")
+    if cfg.pattern == PATTERN_HALVING_DOUBLING and cfg.world & (cfg.world - 1):
+        raise ValueError("halving-doubling needs a power-of-two world")
     if len(elems) == 0:
         raise ValueError("no tensors")
     if any(e <= 0 for e in elems):

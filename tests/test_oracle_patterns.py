@@ -27,7 +27,7 @@ def test_worked_example_values():
             assert (grads[w][0] == np.float32(ex[key])).all()
 
 
-@pytest.mark.parametrize("W", [1, 2, 4, 8, 16])
+@pytest.mark.parametrize("W", [1, 2, 4, 8, 16, 32, 64])
 def test_halving_doubling_formula_equals_protocol_simulation(W):
     rng = np.random.default_rng(W)
     for n in (4, 5, 16, 64, 67, 4 * W * 3 + 1):
@@ -88,7 +88,7 @@ def test_integer_inputs_are_exact_in_every_order(pattern, dtype):
 
 
 def test_halving_doubling_needs_a_power_of_two():
-    for W in (3, 5, 32):
+    for W in (3, 5, 24, 48):
         with pytest.raises(ValueError):
             build_plan(Config(W, F32, 0, pattern=PATTERN_HALVING_DOUBLING), [16])
     with pytest.raises(ValueError):
