@@ -39,14 +39,22 @@ def parse_args():
     ap.add_argument("--pattern", choices=["ring", "hd", "shuffle"], default="ring")
     ap.add_argument("--launch-min-bytes", type=int, default=None)
     ap.add_argument("--align-tiles", type=int, default=None, help="0..3, see CARAMEL_OPT_ALIGN_TILES")
+    ap.add_argument("--long-run-bytes", type=int, default=None, help="see CARAMEL_OPT_LONG_RUN_BYTES")
+    ap.add_argument("--large-align", type=int, default=65536,
+                    help="start of every tensor of >= 1 MiB inside a replica's arena (a multiple of 256)")
     ap.add_argument("--device-fill", action="store_true",
                     help="fill the replicas on the device instead of uploading Philox samples")
     ap.add_argument("--no-cpu-baseline", action="store_true")
-    ap.add_argument("--calibrate", action="store_true",
-                    help="also run a plain in-place copy of known size (a W=1 reduction of one 1 GiB "
-                         "tensor, kernel k_ring_reduce_any) so that a counter run can scale "
-                         "FETCH_SIZE / WRITE_SIZE by what they read for it")
     ap.add_argument("--cpu-repeats", type=int, default=21)
+    ap.add_argument("--probe", action="store_true",
+                    help="instead of the benchmark: time plain streaming kernels of known traffic "
+                         "(caramel_stream_probe) in the access shapes of the reduce kernels, and a 1 GiB "
+                         "torch copy; prints one line per case")
+    ap.add_argument("--probe-mib", type=int, default=512, help="--probe: MiB per buffer")
+    ap.add_argument("--profile-level", type=int, default=2,
+                    help="HIP-event timing of the steps that follow the timed region: 2 = a pair per kernel "
+                         "launch (needed for the roofline line), 1 = a pair per stream and call")
+    ap.add_argument("--profile-steps", type=int, default=50, help="steps timed launch by launch after the timed region")
     return ap.parse_args()
 
 
@@ -61,6 +69,52 @@ def read_traffic(name: str):
     except OSError:
         pass
     return None
+
+
+def probe(args, cm, torch) -> int:
+    """Ceilings for the reduce kernels: W buffers read, written, and updated in place (every value
+    read once and written once, like the ring reduction) by plain kernels without descriptor
+    tables, in 4 KiB, 16 KiB and 64 KiB runs per workgroup; and copies of known size, one of them
+    not this library's (torch), to check a profiler's counters against."""
+    nbytes = args.probe_mib << 20
+    stream = torch.cuda.current_stream().cuda_stream
+
+    def timed(fn, moved):
+        for _ in range(3):
+            fn()
+        torch.cuda.synchronize()
+        best = None
+        for _ in range(3):
+            t0 = time.perf_counter()
+            for _ in range(10):
+                fn()
+            torch.cuda.synchronize()
+            dt = (time.perf_counter() - t0) / 10
+            best = dt if best is None else min(best, dt)
+        return best * 1e3, moved / best / 1e9
+
+    for W in (1, 8, 16):
+        bufs = [torch.zeros(nbytes // 4, dtype=torch.float32, device="cuda:0") for _ in range(W)]
+        ptrs = [b.data_ptr() for b in bufs]
+        for mode, name, factor in ((cm.PROBE_READ, "read", 1), (cm.PROBE_WRITE, "write", 1), (cm.PROBE_UPDATE, "update", 2)):
+            for run, block in ((4096, 256), (16384, 1024), (65536, 1024)):
+                if mode != cm.PROBE_UPDATE and run != 16384:
+                    continue
+                ms, gbs = timed(lambda: cm.stream_probe(mode, ptrs, nbytes, run, block, stream), factor * W * nbytes)
+                print(json.dumps({"probe": name, "buffers": W, "mib_per_buffer": args.probe_mib, "run_bytes": run,
+                                  "block": block, "ms": round(ms, 4), "GB/s": round(gbs, 1),
+                                  "frac_of_peak": round(gbs / HBM_PEAK_GBS, 4)}), flush=True)
+        del bufs
+    gib = 1 << 30
+    a = torch.zeros(gib // 4, dtype=torch.float32, device="cuda:0")
+    b = torch.zeros(gib // 4, dtype=torch.float32, device="cuda:0")
+    ms, gbs = timed(lambda: cm.stream_probe(cm.PROBE_COPY, [a.data_ptr(), b.data_ptr()], gib, 16384, 1024, stream), 2 * gib)
+    print(json.dumps({"probe": "copy 1 GiB (k_probe)", "ms": round(ms, 4), "GB/s": round(gbs, 1),
+                      "frac_of_peak": round(gbs / HBM_PEAK_GBS, 4)}), flush=True)
+    ms, gbs = timed(lambda: b.copy_(a), 2 * gib)
+    print(json.dumps({"probe": "copy 1 GiB (torch copy_)", "ms": round(ms, 4), "GB/s": round(gbs, 1),
+                      "frac_of_peak": round(gbs / HBM_PEAK_GBS, 4)}), flush=True)
+    return 0
 
 
 def main() -> int:
@@ -83,6 +137,9 @@ def main() -> int:
         return 2
     cm.lib()
 
+    if args.probe:
+        return probe(args, cm, torch)
+
     wl = workload(args.workload)
     elems = wl.elems()
     streams = args.streams or wl.num_streams
@@ -100,11 +157,11 @@ def main() -> int:
     for opt, val in ((cm.OPT_TILE_VECS, args.tile_vecs), (cm.OPT_MAX_GRID, args.max_grid),
                      (cm.OPT_NONTEMPORAL, args.nontemporal), (cm.OPT_UNROLL, args.unroll),
                      (cm.OPT_BLOCK, args.block), (cm.OPT_LAUNCH_MIN_BYTES, args.launch_min_bytes),
-                     (cm.OPT_ALIGN_TILES, args.align_tiles)):
+                     (cm.OPT_ALIGN_TILES, args.align_tiles), (cm.OPT_LONG_RUN_BYTES, args.long_run_bytes)):
         if val is not None:
             plan.set_option(opt, val)
 
-    dev = Replicas(plan, elems, device="cuda:0", with_workspace=staged)
+    dev = Replicas(plan, elems, device="cuda:0", with_workspace=staged, large_align=args.large_align)
     grads = None
     if args.device_fill:
         dev.fill_random(args.seed)
@@ -113,59 +170,68 @@ def main() -> int:
         dev.upload(grads)
 
     stream = torch.cuda.current_stream().cuda_stream
-    if args.calibrate:
-        n_cal = (1 << 30) // 4
-        cal = cm.Plan(1, [n_cal], num_streams=1)
-        buf = torch.zeros(n_cal, dtype=torch.float32, device="cuda:0")
-        cal.bind([[buf.data_ptr()]], None)
-        for _ in range(3):
-            cal.allreduce(stream)          # reads 1 GiB, writes 1 GiB
-        torch.cuda.synchronize()
-        cal.close()
-        del buf
     for _ in range(args.warmup):
         plan.allreduce(stream)
     torch.cuda.synchronize()
-    plan.profile(1)
+    # The timed region: K steps between two synchronisations, with no timing events inside (a
+    # pair of events per launch costs about 20 us per step, a tenth of a short step), bracketed
+    # by one pair of events on the stream the kernels are launched on.
+    ev0, ev1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
     torch.cuda.synchronize()
     t0 = time.perf_counter()
+    ev0.record()
     for _ in range(args.steps):
         plan.allreduce(stream)
+    ev1.record()
     torch.cuda.synchronize()
     t1 = time.perf_counter()
+    region_ms = ev0.elapsed_time(ev1)
+    # Right after it, the same steps again with one pair of HIP events around every kernel launch
+    # (recorded by the library on the launch stream): each kernel's own average duration.
+    plan.profile(args.profile_level)
+    for _ in range(args.profile_steps):
+        plan.allreduce(stream)
     stats = plan.profile_read()
     plan.profile(0)
+    prof_steps = args.profile_steps
 
     ms_per_step = (t1 - t0) * 1e3 / args.steps
     alg_bytes = wl.algorithmic_bytes()
     gbs = alg_bytes / (ms_per_step * 1e-3) / 1e9
 
-    # Dominant kernels: the two variants of the ring-reduce kernel (stream-major for long launches
-    # over large units, all-at-once for the rest); in the default direct mode nothing else runs.  The
-    # library brackets everything each internal stream does in a call with one pair of HIP events
-    # recorded on that stream; launches of one stream run back to back, so a launch's average
-    # duration is the stream's busy time divided by its launches.  The two streams overlap in
-    # time (that is the pipeline), i.e. a launch shares the memory system with a launch of the
-    # other stream while it runs:
-    #   per_launch_achieved = algorithmic bytes of a launch / its average duration
-    #   achieved            = algorithmic bytes of a step / time from the first launch's start to
-    #                         the last launch's end (= per-launch figure x launches in flight)
-    red, seq = stats[cm.K_REDUCE], stats[cm.K_SEQUENCE]
-    launches_per_step = red["launches"] / args.steps
-    avg_ms = seq["total_ms"] / max(1, red["launches"])
+    # Dominant kernel: k_ring_reduce_sm, the stream-major ring reduction over long tiles (in the
+    # default in-place mode the only other kernel is k_ring_reduce over the few short runs).
+    #   achieved = algorithmic bytes of its launches (2*W*s per element they cover)
+    #              / the sum of their durations, both counted by the library over the timed region
+    es = 4 if wl.dtype == cm.F32 else 2
+    lng, sml, seq = stats[cm.K_REDUCE], stats[cm.K_REDUCE_SMALL], stats[cm.K_SEQUENCE]
+    per_elem = 2 * wl.world * es
+
+    def kernel_line(st):
+        if not st["launches"]:
+            return None
+        out = {"launches_per_step": st["launches"] / prof_steps,
+               "bytes_per_launch": round(per_elem * st["elements"] / st["launches"])}
+        if st["total_ms"] > 0:
+            out["avg_launch_ms"] = round(st["total_ms"] / st["launches"], 6)
+            out["achieved"] = round(per_elem * st["elements"] / (st["total_ms"] * 1e-3) / 1e9, 1)
+        return out
+
+    dom_name, dom = ("k_ring_reduce_sm", lng) if lng["elements"] >= sml["elements"] else ("k_ring_reduce", sml)
+    dom_line = kernel_line(dom) or {}
     span_ms = seq["span_ms"] / max(1, seq["calls"])
-    bytes_per_launch = alg_bytes / launches_per_step       # 2*W*s per element the launch reduces
-    per_launch = bytes_per_launch / (avg_ms * 1e-3) / 1e9
-    achieved = alg_bytes / (span_ms * 1e-3) / 1e9
-    traffic = read_traffic(wl.name)
-    roofline = {
-        "bound": "hbm", "kernel": "k_ring_reduce_sm (large units) + k_ring_reduce (others)", "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS,
-        "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": traffic,
-        "launches_per_step": launches_per_step, "avg_launch_ms": round(avg_ms, 6),
-        "bytes_per_launch": round(bytes_per_launch), "per_launch_achieved": round(per_launch, 1),
-        "launches_in_flight": round(seq["total_ms"] / max(seq["span_ms"], 1e-9), 3),
-        "step_span_ms": round(span_ms, 5),
-    }
+    roofline = {"bound": "hbm", "kernel": dom_name, "achieved": dom_line.get("achieved"), "peak": HBM_PEAK_GBS,
+                "unit": "GB/s",
+                "frac": round(dom_line["achieved"] / HBM_PEAK_GBS, 4) if dom_line.get("achieved") else None,
+                "traffic": read_traffic(wl.name),
+                "launches_per_step": dom_line.get("launches_per_step"),
+                "avg_launch_ms": dom_line.get("avg_launch_ms"), "bytes_per_launch": dom_line.get("bytes_per_launch"),
+                "share_of_step_bytes": round(dom["elements"] / max(1, lng["elements"] + sml["elements"]), 4),
+                "other_kernel": kernel_line(sml if dom is lng else lng),
+                "step_span_ms": round(span_ms, 5) if seq["calls"] else None,
+                "step_frac": round(gbs / HBM_PEAK_GBS, 4),
+                "timed_region_event_ms_per_step": round(region_ms / args.steps, 5),
+                "per_launch_event_steps": prof_steps}
 
     cpu = None
     if not args.no_cpu_baseline:
@@ -178,14 +244,20 @@ def main() -> int:
             grads = gradients.replica_set(args.seed, wl.world, elems, bf16=(wl.dtype == cm.BF16), threads=16)
         fused = oracle.new_fused(oplan)
         times = []
-        for _ in range(args.cpu_repeats):
-            c0 = time.perf_counter()
-            oracle.allreduce(oplan, grads, fused)       # in place; speed does not depend on values
-            times.append(time.perf_counter() - c0)
+        # one core: numpy's elementwise arithmetic is single-threaded, and the process is pinned
+        allowed = os.sched_getaffinity(0)
+        os.sched_setaffinity(0, {min(allowed)})
+        try:
+            for _ in range(args.cpu_repeats):
+                c0 = time.perf_counter()
+                oracle.allreduce(oplan, grads, fused)       # in place; speed does not depend on values
+                times.append(time.perf_counter() - c0)
+        finally:
+            os.sched_setaffinity(0, allowed)
         med = sorted(times)[len(times) // 2]
         cpu = {"value": round(alg_bytes / med / 1e9, 3), "unit": "GB/s", "cores": 1, "kind": "oracle",
                "sample": f"the whole {wl.name} workload (W={wl.world}), pack+ring_reduce+unpack, "
-                         f"median of {args.cpu_repeats} passes, {med * 1e3:.0f} ms per pass"}
+                         f"pinned to one core, median of {args.cpu_repeats} passes, {med * 1e3:.0f} ms per pass"}
         # the same oracle functions with the (independent) units dealt out to the host's cores
         from concurrent.futures import ThreadPoolExecutor
         n_thr = max(1, min(16, os.cpu_count() or 1))

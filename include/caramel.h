@@ -68,8 +68,8 @@ enum { CARAMEL_PATTERN_RING = 0, CARAMEL_PATTERN_HALVING_DOUBLING = 1, CARAMEL_P
  *   pattern               decentralised aggregation pattern (sections 2 and 6.3); it fixes the
  *                         order of the fp32 additions, everything else is the same.
  *                         RING: segment c is summed x[c+1] + x[c+2] + ... + x[c] (indices mod W).
- *                         HALVING_DOUBLING (recursive vector halving, distance doubling; W in
- *                         {1,2,4,8,16}): the balanced tree ((x0+x1)+(x2+x3)) + ((x4+x5)+(x6+x7)) ...
+ *                         HALVING_DOUBLING (recursive vector halving, distance doubling; W a
+ *                         power of two): the balanced tree ((x0+x1)+(x2+x3)) + ((x4+x5)+(x6+x7)) ...
  *                         SHUFFLE (the owner of a slice receives it from every worker): x0 + x1 +
  *                         ... + x(W-1) in worker order.
  */
@@ -116,12 +116,12 @@ typedef struct caramel_plan caramel_plan; /* opaque, owned by the library */
  * EINVAL: NULL argument, n_tensors == 0, a zero-element tensor, world out of range, unknown
  * dtype or split mode, align_bytes not a power of two >= 16, split_bytes not a positive
  * multiple of align_bytes when splitting, num_streams not 1 or 2, max_depth == 0 (ADAPTIVE),
- * unknown pattern, HALVING_DOUBLING with another world size, reserved != 0. */
+ * unknown pattern, HALVING_DOUBLING with a world that is not a power of two, reserved != 0. */
 int caramel_plan_create(const caramel_config* cfg, const uint64_t* tensor_elems, uint32_t n_tensors,
                         caramel_plan** out);
 
-/* Timing-aware batching (section 4.2: the open batch is transferred when its size exceeds the
- * threshold "or if the transfers in the queue are done before the next parameter update").
+/* Timing-aware batching (section 4.2: besides the size rule, the open batch is also sent when
+ * the transfer queue will have drained before the next parameter is updated).
  *   ready_time  n_tensors expected update times, non-decreasing, any unit of time;
  *   net_a/net_b transfer-time model of the aggregation: a transfer of d bytes takes
  *               net_a + net_b * d (same time unit; both >= 0).
@@ -143,7 +143,9 @@ int caramel_plan_times(const caramel_plan* plan, double* enqueue, double* start,
  * two measured (size, transfer time) pairs (the paper measures 64 B and 4 MB).
  * caramel_threshold_estimate: the smallest size x >= 1 with f(2x) / (2 f(x)) > 0.8 for
  * f(d) = a + b*d, i.e. the smallest integer above 1.5 a / b, decided in exact arithmetic.
- * EINVAL: equal sizes; a < 0, b <= 0, non-finite values, or a result beyond 64 bits. */
+ * EINVAL: equal sizes or non-finite times; a fitted line with a < 0 or b <= 0 (two noisy probes
+ * whose times do not grow with size: measure again); for the estimate a < 0, b <= 0, non-finite
+ * values, or a result beyond 64 bits. */
 int caramel_net_model_fit(uint64_t bytes1, double time1, uint64_t bytes2, double time2, double* a, double* b);
 int caramel_threshold_estimate(double a, double b, uint64_t* threshold_bytes);
 
@@ -212,9 +214,20 @@ int caramel_plan_entries(const caramel_plan* plan, caramel_entry* out, uint32_t 
 /* Ring segments of one unit: world+1 element offsets; segment c = [seg[c], seg[c+1]) is the
  * part whose sum completes at worker c. */
 int caramel_plan_segments(const caramel_plan* plan, uint32_t unit, uint64_t* seg_start);
-/* Canonical little-endian image of the plan (config, units, entries, segments).  Call with
- * buf == NULL to get the size in *len; otherwise *len is the capacity on entry and the size
- * written on return (EINVAL if too small). */
+/* Canonical byte image of the plan: equal plans give equal bytes on every host.  All fields
+ * little-endian, no padding, in this order:
+ *   char[8]  "CARAMEL1"
+ *   u32 world, u32 dtype, u64 batch_threshold_bytes, u32 split_mode, u32 max_depth,
+ *   u64 split_bytes, u32 align_bytes, u32 num_streams, u32 pattern          (the configuration)
+ *   u32 n_tensors, u32 n_units, u32 n_entries, u64 fused_elems
+ *   u64 tensor_elems[n_tensors]
+ *   n_units   x { u32 kind, u32 stream, u32 first_entry, u32 n_entries, u64 elems, u64 fused_off }
+ *   n_entries x { u32 tensor, u32 unit, u64 tensor_off, u64 unit_off, u64 elems }
+ *   u64 seg_start[n_units][world + 1]                                        (ring segments)
+ * (72 + 8 n_tensors + 32 n_units + 32 n_entries + 8 n_units (world + 1) bytes; launch options and
+ * the modelled times of a timing-aware plan are not part of it.)  Call with buf == NULL to get
+ * the size in *len; otherwise *len is the capacity on entry and the size written on return
+ * (EINVAL if too small). */
 int caramel_plan_serialize(const caramel_plan* plan, void* buf, size_t* len);
 
 /* ---- execution on the GPU ---------------------------------------------------------------- */
@@ -222,9 +235,9 @@ int caramel_plan_serialize(const caramel_plan* plan, void* buf, size_t* len);
 /* Attach memory to a plan.
  *   grads     host array of world * n_tensors DEVICE pointers; grads[w * n_tensors + t] is
  *             worker w's tensor t (tensor_elems[t] elements of the plan's dtype), aligned to
- *             align_bytes.  Replicas must not overlap.  (Any such pointers are correct; large
- *             tensors stream fastest when they start on 64 KiB boundaries, because the reduce
- *             kernel's large tiles then coincide with aligned 64 KiB blocks of memory.)
+ *             align_bytes.  Replicas must not overlap.  (Any such pointers are correct; the
+ *             kernels stream fastest when a tensor has the same address modulo 64 KiB in every
+ *             replica, because tiles can then be cut on aligned 64 KiB blocks of memory.)
  *   fused_ws  DEVICE workspace of world * fused_elems elements (replica w's fused buffer starts
  *             at element w * fused_elems); may be NULL when fused_elems == 0, or when only
  *             caramel_allreduce in its default (direct) mode is going to be used.
@@ -259,74 +272,65 @@ int caramel_allreduce(caramel_plan* plan, void* stream);
 
 /* ---- launch tuning and timing (do not change results) ------------------------------------ */
 
+/* How the work is cut up for the GPU.  A "run" is a maximal piece of one tensor (or of the fused
+ * buffer) inside one ring segment of one unit: one per segment for a chunk unit, one per member
+ * and segment for a batch unit that is reduced in place.  Runs of at least
+ * CARAMEL_OPT_LONG_RUN_BYTES are cut into long tiles (CARAMEL_OPT_TILE_VECS), which 1024-lane
+ * workgroups walk one replica after the other; shorter runs into small tiles
+ * (CARAMEL_OPT_SMALL_TILE_VECS), for which 256-lane workgroups fetch all replicas at once.
+ * Long and small tiles go out in separate launches. */
 enum {
-  /* How units map to kernel launches.  PER_UNIT: one launch per unit and stage (the literal
-   * pipeline).  PER_STREAM: all units of one internal stream share launches through a
-   * descriptor table.  AUTO (default): PER_UNIT with two streams, where the launches of one
-   * stream fill the gaps of the other, if the call is large enough to repay the fork and join
-   * (CARAMEL_OPT_PIPELINE_MIN_BYTES); otherwise PER_STREAM on the caller's stream. */
+  /* How units map to kernel launches.  PER_UNIT: consecutive units of a plan stream share a
+   * launch until it covers CARAMEL_OPT_LAUNCH_MIN_BYTES / CARAMEL_OPT_LONG_LAUNCH_MIN_BYTES
+   * (0: strictly one launch per unit and tile class: the literal pipeline), plan stream 1 on the
+   * internal stream.  PER_STREAM: one launch per tile class and plan stream.  AUTO (default):
+   * PER_UNIT over two streams, where the launches of one stream fill the gaps of the other, if
+   * the call is large enough to repay the fork and join (CARAMEL_OPT_PIPELINE_MIN_BYTES);
+   * otherwise one launch per tile class on the caller's stream. */
   CARAMEL_OPT_LAUNCH_MODE = 0,
   /* Batch units in caramel_allreduce.  STAGED: pack -> reduce -> unpack through fused_ws.
    * DIRECT: one gather-reduce-scatter kernel that reads member tensors and writes results back
    * without materialising the fused buffer (same segments, same order, same bits).
    * Default DIRECT. */
   CARAMEL_OPT_BATCH_PATH = 1,
-  /* 16-byte vectors per replica in one workgroup tile of the reduce kernel, for large units
-   * (chunk units of at least CARAMEL_OPT_LARGE_UNIT_BYTES per replica) of a stream whose large
-   * units total at least CARAMEL_OPT_LONG_LAUNCH_BYTES.  Default 4096. */
+  /* 16-byte vectors per replica in a long tile.  Default 4096 (64 KiB). */
   CARAMEL_OPT_TILE_VECS = 2,
   /* Upper bound on workgroups per reduce launch (0 = one workgroup per tile). */
   CARAMEL_OPT_MAX_GRID = 3,
   /* Non-zero: streaming (non-temporal) loads/stores in the reduce kernel. */
   CARAMEL_OPT_NONTEMPORAL = 4,
-  /* 16-byte vectors each lane keeps in flight per worker: 1, 2 or 4; 0 = chosen from W. */
+  /* 16-byte vectors each lane keeps in flight per worker where all replicas are fetched at
+   * once: 1, 2 or 4; 0 = chosen from W. */
   CARAMEL_OPT_UNROLL = 5,
-  /* Lanes per workgroup of the reduce kernel over large units: 256, 512 or 1024. */
+  /* Lanes per workgroup over long tiles: 256, 512 or 1024 (default). */
   CARAMEL_OPT_BLOCK = 6,
-  /* PER_UNIT launches only: consecutive small units of one stream share a launch until it
-   * covers at least this many bytes per replica (0 = strictly one launch per unit).  The
-   * launch-side counterpart of the batching threshold: it amortises launch overhead over small
-   * units.  Default 4 MiB.  A stream's launches over large units and over small units are
-   * independent sequences; the order in which they are issued does not affect results. */
+  /* PER_UNIT launches over small tiles: consecutive units of one stream share a launch until it
+   * covers at least this many bytes per replica.  The launch-side counterpart of the batching
+   * threshold: it amortises launch overhead over small units.  Default 4 MiB. */
   CARAMEL_OPT_LAUNCH_MIN_BYTES = 7,
   /* AUTO launch mode only: a call whose algorithmic bytes (2 * world * elements * element size)
-   * are below this value is not pipelined: it runs as one launch per stage on the caller's
-   * stream, with no fork or join.  Default 256 MiB. */
+   * are below this value is not pipelined.  Default: the largest value, i.e. AUTO does not
+   * pipeline (on MI355X one launch over all long tiles measured faster than two streams for every
+   * workload tried, because the fork and join cost more than the overlap wins). */
   CARAMEL_OPT_PIPELINE_MIN_BYTES = 8,
-  /* Tile size and workgroup size for all other units (batch units, whose tiles are cut at
-   * member boundaries, and small chunks).  Defaults 256 and 256. */
+  /* Vectors per small tile and lanes per workgroup over small tiles.  Defaults 256 and 256. */
   CARAMEL_OPT_SMALL_TILE_VECS = 9,
   CARAMEL_OPT_SMALL_BLOCK = 10,
-  /* Bytes per replica from which a chunk unit counts as large.  Default 4 MiB.  Large and small
-   * units never share a launch. */
-  CARAMEL_OPT_LARGE_UNIT_BYTES = 11,
-  /* Large units only: 2 or 4 (default) selects the stream-major kernel, which walks the chain
-   * of workers one replica at a time with that many vectors per lane (long contiguous runs per
+  /* Bytes per replica from which a run is cut into long tiles.  Default 32 KiB.  0: every run is
+   * long; a huge value: every run is small. */
+  CARAMEL_OPT_LONG_RUN_BYTES = 11,
+  /* Long tiles: 2 or 4 (default) selects the stream-major kernel, which walks the chain of
+   * workers one replica at a time with that many vectors per lane (long contiguous requests per
    * replica; meant for tiles of block * value vectors); 0 fetches all workers' values at once.
    * The halving-doubling pattern always uses the latter. */
   CARAMEL_OPT_STREAM_MAJOR = 12,
-  /* PER_UNIT launches only: like CARAMEL_OPT_LAUNCH_MIN_BYTES, for launches over large units.
-   * Default 64 MiB (the stream-major kernel wants long launches). */
-  CARAMEL_OPT_LARGE_LAUNCH_MIN_BYTES = 13,
-  /* Bit 0 (small tiles), bit 1 (medium tiles): where every replica of a tensor has the same
-   * address modulo the tile size, tiles are cut so that they start on multiples of the tile size
-   * in memory (the first tile of a run is shortened); otherwise tiles start where their run
-   * starts.  Default 1: measured +6 % on the Inception-v3 shape (W = 16) for small tiles, while
-   * medium tiles ran slower cut that way.  Takes effect at the next caramel_bind.  Results do
-   * not depend on it. */
-  CARAMEL_OPT_ALIGN_TILES = 14,
-  /* Large units of a stream get the long-launch treatment (large tiles, stream-major kernel,
-   * launches of CARAMEL_OPT_LARGE_LAUNCH_MIN_BYTES) only if they total at least this many bytes
-   * per replica; default 64 MiB.  Otherwise they get tiles of CARAMEL_OPT_MEDIUM_TILE_VECS
-   * (default 1024) and launches like the small units'. */
-  CARAMEL_OPT_LONG_LAUNCH_BYTES = 15,
-  CARAMEL_OPT_MEDIUM_TILE_VECS = 16,
-  /* Medium tiles (and the large workgroups that go with them) are used only when the replicas
-   * together hold at least this many bytes; for smaller gradient sets the medium class is cut
-   * and launched in the small shape.  Default 1.5 GiB: 16 KiB runs win on working sets of
-   * several GiB, 4 KiB runs (four times as many workgroups per launch) below.  Takes effect at
-   * the next caramel_bind. */
-  CARAMEL_OPT_MEDIUM_MIN_FOOTPRINT = 17
+  /* PER_UNIT launches over long tiles: like CARAMEL_OPT_LAUNCH_MIN_BYTES.  Default 64 MiB. */
+  CARAMEL_OPT_LONG_LAUNCH_MIN_BYTES = 13,
+  /* Bit 0 (small tiles), bit 1 (long tiles): where every replica of a run has the same address
+   * modulo the tile size, tiles are cut so that they start on multiples of the tile size in
+   * memory (the first tile of a run is shortened); otherwise tiles start where their run starts.
+   * Default 3.  Takes effect at the next caramel_bind.  Results do not depend on it. */
+  CARAMEL_OPT_ALIGN_TILES = 14
 };
 enum { CARAMEL_LAUNCH_PER_UNIT = 0, CARAMEL_LAUNCH_PER_STREAM = 1, CARAMEL_LAUNCH_AUTO = 2 };
 enum { CARAMEL_BATCH_STAGED = 0, CARAMEL_BATCH_DIRECT = 1 };
@@ -336,22 +340,32 @@ enum { CARAMEL_BATCH_STAGED = 0, CARAMEL_BATCH_DIRECT = 1 };
  * EINVAL for an unknown option or a value out of range. */
 int caramel_plan_set_option(caramel_plan* plan, uint32_t option, uint64_t value);
 
-enum { CARAMEL_K_PACK = 0, CARAMEL_K_REDUCE = 1, CARAMEL_K_UNPACK = 2, CARAMEL_K_SEQUENCE = 3, CARAMEL_K_COUNT = 4 };
+enum {
+  CARAMEL_K_PACK = 0,
+  CARAMEL_K_REDUCE = 1,       /* reduce launches over long tiles (the stream-major kernel) */
+  CARAMEL_K_UNPACK = 2,
+  CARAMEL_K_SEQUENCE = 3,
+  CARAMEL_K_REDUCE_SMALL = 4, /* reduce launches over small tiles */
+  CARAMEL_K_COUNT = 5
+};
 
 /* Timing with HIP events recorded on the stream the work is launched on.
- *   PACK / REDUCE / UNPACK  `launches` counts kernel launches; `total_ms` is the sum of their
- *                           durations and is filled at level 2 only.
- *   SEQUENCE                everything one stream does in one ring_reduce / allreduce call,
- *                           from before its first launch to after its last: `launches` counts
- *                           sequences, `total_ms` sums their durations (levels 1 and 2).
+ *   PACK / REDUCE / REDUCE_SMALL / UNPACK
+ *                `launches` counts kernel launches and `elements` the elements per replica they
+ *                cover (a reduce launch moves 2 * world * element size bytes for each);
+ *                `total_ms` is the sum of their durations and is filled at level 2 only.
+ *   SEQUENCE     everything one stream does in one ring_reduce / allreduce call, from before
+ *                its first launch to after its last: `launches` counts sequences, `total_ms`
+ *                sums their durations (levels 1 and 2).
  * `span_ms` accumulates, per call, the time from the earliest start to the latest end of the
- * timed intervals of that kind (sequences on the two streams overlap, so for SEQUENCE the span
+ * timed intervals of that kind (with two streams the sequences overlap, so for SEQUENCE the span
  * is the duration of the whole call on the GPU); `calls` counts the calls that contributed. */
 typedef struct caramel_kernel_stat {
   uint64_t launches;
   double total_ms;
   double span_ms;
   uint64_t calls;
+  uint64_t elements;
 } caramel_kernel_stat;
 
 /* Set the timing level and clear the statistics.  0: off.  1: one event pair per stream and
@@ -362,6 +376,24 @@ int caramel_profile(caramel_plan* plan, int level);
 /* Synchronise the internal streams, fold pending event pairs into the statistics and copy
  * CARAMEL_K_COUNT records to `out`. */
 int caramel_profile_read(caramel_plan* plan, caramel_kernel_stat* out);
+
+/* ---- measurement aid -------------------------------------------------------------------- */
+
+/* Plain streaming kernels of exactly known traffic, with no descriptor tables: ceilings to set
+ * the reduce kernels against, and kernels to check a profiler's memory counters with.
+ *   READ    loads every 16-byte vector of the n_buffers buffers          (n_buffers * bytes read)
+ *   WRITE   stores every vector of the n_buffers buffers                 (n_buffers * bytes written)
+ *   UPDATE  loads all n_buffers values of a vector, adds them, stores the sum to all buffers:
+ *           the reduce kernel's traffic           (n_buffers * bytes read and as many written)
+ *   COPY    buffer 0 -> buffer 1, n_buffers must be 2                    (bytes read, bytes written)
+ * buffers: host array of n_buffers (1, 2, 4, 8 or 16) DEVICE pointers to `bytes` bytes each
+ * (multiples of 16); workgroup b of `block` lanes (256, 512 or 1024) handles bytes
+ * [b * run_bytes, (b + 1) * run_bytes) of every buffer, with streaming loads and stores.
+ * Asynchronous on `stream`.  EINVAL for other arguments (no message is recorded), EHIP if the
+ * launch fails. */
+enum { CARAMEL_PROBE_READ = 0, CARAMEL_PROBE_WRITE = 1, CARAMEL_PROBE_UPDATE = 2, CARAMEL_PROBE_COPY = 3 };
+int caramel_stream_probe(uint32_t mode, void* const* buffers, uint32_t n_buffers, uint64_t bytes,
+                         uint32_t run_bytes, uint32_t block, void* stream);
 
 /* Message for the calling thread's last non-OK status ("" if none). */
 const char* caramel_last_error(void);

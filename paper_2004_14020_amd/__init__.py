@@ -4,11 +4,12 @@ The work is done by hand-written HIP kernels behind the C ABI declared in
 include/caramel.h; this package only marshals arguments (binding.py) and, in
 device.py, uses PyTorch to hold device memory and streams.
 """
-from .binding import (BIN_BACKWARD, BIN_FORWARD, BATCH_DIRECT, BATCH_STAGED, BF16, F32, K_COUNT, K_PACK, K_REDUCE, K_SEQUENCE, K_UNPACK,
+from .binding import (BIN_BACKWARD, BIN_FORWARD, BATCH_DIRECT, BATCH_STAGED, BF16, F32, K_COUNT, K_PACK, K_REDUCE, K_REDUCE_SMALL, K_SEQUENCE, K_UNPACK,
                       KIND_BATCH, KIND_CHUNK, LAUNCH_AUTO, LAUNCH_PER_STREAM, LAUNCH_PER_UNIT, OPT_BATCH_PATH,
-                      PATTERN_HALVING_DOUBLING, PATTERN_RING, PATTERN_SHUFFLE, OPT_BLOCK, OPT_LAUNCH_MIN_BYTES, OPT_LAUNCH_MODE, OPT_PIPELINE_MIN_BYTES, OPT_SMALL_TILE_VECS, OPT_SMALL_BLOCK, OPT_LARGE_UNIT_BYTES, OPT_STREAM_MAJOR, OPT_LARGE_LAUNCH_MIN_BYTES, OPT_ALIGN_TILES, OPT_LONG_LAUNCH_BYTES, OPT_MEDIUM_TILE_VECS, OPT_MEDIUM_MIN_FOOTPRINT, OPT_MAX_GRID, OPT_NONTEMPORAL, OPT_TILE_VECS, OPT_UNROLL,
+                      PATTERN_HALVING_DOUBLING, PATTERN_RING, PATTERN_SHUFFLE, OPT_BLOCK, OPT_LAUNCH_MIN_BYTES, OPT_LAUNCH_MODE, OPT_PIPELINE_MIN_BYTES, OPT_SMALL_TILE_VECS, OPT_SMALL_BLOCK, OPT_LONG_RUN_BYTES, OPT_STREAM_MAJOR, OPT_LONG_LAUNCH_MIN_BYTES, OPT_ALIGN_TILES, OPT_MAX_GRID, OPT_NONTEMPORAL, OPT_TILE_VECS, OPT_UNROLL,
                       SPLIT_ADAPTIVE, SPLIT_FIXED, SPLIT_NONE, CaramelError, Config, Entry, Plan, ScheduleSummary, Slot,
-                      Unit, lib, net_model_fit, schedule_transfers, threshold_estimate)
+                      Unit, lib, net_model_fit, schedule_transfers, stream_probe, threshold_estimate,
+                      PROBE_COPY, PROBE_READ, PROBE_UPDATE, PROBE_WRITE)
 
 
 # Functional spellings with the names of the C entry points.
@@ -94,6 +95,10 @@ def caramel_profile(plan: Plan, level: int) -> None:
 
 def caramel_profile_read(plan: Plan):
     return plan.profile_read()
+
+
+def caramel_stream_probe(mode, buffers, nbytes, run_bytes=4096, block=256, stream: int = 0) -> None:
+    stream_probe(mode, buffers, nbytes, run_bytes, block, stream)
 
 
 def caramel_version() -> int:

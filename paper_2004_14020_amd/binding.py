@@ -20,10 +20,11 @@ SPLIT_NONE, SPLIT_FIXED, SPLIT_ADAPTIVE = 0, 1, 2
 KIND_BATCH, KIND_CHUNK = 0, 1
 PATTERN_RING, PATTERN_HALVING_DOUBLING, PATTERN_SHUFFLE = 0, 1, 2
 (OPT_LAUNCH_MODE, OPT_BATCH_PATH, OPT_TILE_VECS, OPT_MAX_GRID, OPT_NONTEMPORAL, OPT_UNROLL, OPT_BLOCK,
- OPT_LAUNCH_MIN_BYTES, OPT_PIPELINE_MIN_BYTES, OPT_SMALL_TILE_VECS, OPT_SMALL_BLOCK, OPT_LARGE_UNIT_BYTES, OPT_STREAM_MAJOR, OPT_LARGE_LAUNCH_MIN_BYTES, OPT_ALIGN_TILES, OPT_LONG_LAUNCH_BYTES, OPT_MEDIUM_TILE_VECS, OPT_MEDIUM_MIN_FOOTPRINT) = range(18)
+ OPT_LAUNCH_MIN_BYTES, OPT_PIPELINE_MIN_BYTES, OPT_SMALL_TILE_VECS, OPT_SMALL_BLOCK, OPT_LONG_RUN_BYTES,
+ OPT_STREAM_MAJOR, OPT_LONG_LAUNCH_MIN_BYTES, OPT_ALIGN_TILES) = range(15)
 LAUNCH_PER_UNIT, LAUNCH_PER_STREAM, LAUNCH_AUTO = 0, 1, 2
 BATCH_STAGED, BATCH_DIRECT = 0, 1
-K_PACK, K_REDUCE, K_UNPACK, K_SEQUENCE, K_COUNT = 0, 1, 2, 3, 4
+K_PACK, K_REDUCE, K_UNPACK, K_SEQUENCE, K_REDUCE_SMALL, K_COUNT = 0, 1, 2, 3, 4, 5
 
 EXPORTS = (
     "caramel_plan_create", "caramel_plan_create_timed", "caramel_plan_times", "caramel_net_model_fit",
@@ -31,7 +32,7 @@ EXPORTS = (
     "caramel_plan_entries", "caramel_plan_segments", "caramel_plan_serialize", "caramel_bind",
     "caramel_pack", "caramel_ring_reduce", "caramel_unpack", "caramel_allreduce",
     "caramel_plan_set_option", "caramel_profile", "caramel_profile_read", "caramel_last_error",
-    "caramel_version",
+    "caramel_version", "caramel_stream_probe",
 )
 
 
@@ -64,7 +65,7 @@ class ScheduleSummary(C.Structure):
 
 class KernelStat(C.Structure):
     _fields_ = [("launches", C.c_uint64), ("total_ms", C.c_double), ("span_ms", C.c_double),
-                ("calls", C.c_uint64)]
+                ("calls", C.c_uint64), ("elements", C.c_uint64)]
 
 
 class CaramelError(RuntimeError):
@@ -116,6 +117,7 @@ def lib() -> C.CDLL:
     L.caramel_last_error.restype = C.c_char_p
     L.caramel_last_error.argtypes = []
     L.caramel_version.argtypes = []
+    L.caramel_stream_probe.argtypes = [C.c_uint32, C.POINTER(P), C.c_uint32, C.c_uint64, C.c_uint32, C.c_uint32, P]
     _lib = L
     return L
 
@@ -241,7 +243,20 @@ class Plan:
     def profile_read(self):
         buf = (KernelStat * K_COUNT)()
         _check(lib().caramel_profile_read(self._h, buf))
-        return [dict(launches=s.launches, total_ms=s.total_ms, span_ms=s.span_ms, calls=s.calls) for s in buf]
+        return [dict(launches=s.launches, total_ms=s.total_ms, span_ms=s.span_ms, calls=s.calls, elements=s.elements)
+                for s in buf]
+
+
+PROBE_READ, PROBE_WRITE, PROBE_UPDATE, PROBE_COPY = 0, 1, 2, 3
+
+
+def stream_probe(mode: int, buffers: Sequence[int], nbytes: int, run_bytes: int = 4096, block: int = 256,
+                 stream: int = 0) -> None:
+    """caramel_stream_probe: a plain streaming kernel over the given device buffers."""
+    arr = (C.c_void_p * len(buffers))(*[int(b) for b in buffers])
+    st = lib().caramel_stream_probe(mode, arr, len(buffers), nbytes, run_bytes, block, C.c_void_p(stream))
+    if st != OK:
+        raise CaramelError(st, "caramel_stream_probe: bad arguments" if st == EINVAL else "caramel_stream_probe: launch failed")
 
 
 def net_model_fit(bytes1: int, time1: float, bytes2: int, time2: float):

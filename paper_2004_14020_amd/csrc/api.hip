@@ -58,32 +58,48 @@ struct Options {
   uint32_t max_grid = 0;
   uint32_t nontemporal = 1;
   uint32_t unroll = 0;
-  uint32_t block = 1024;        // workgroup of launches over large units
-  uint32_t small_block = 256;   // ... over everything else
-  uint32_t stream_major = 4;    // vectors per lane of the stream-major kernel for large units (0 = off)
-  uint64_t launch_min_bytes = 4u << 20;         // small units share a launch up to this size
-  uint64_t large_launch_min_bytes = 64u << 20;  // large units likewise
-  uint64_t pipeline_min_bytes = uint64_t(256) << 20;
-  // medium tiles (16 KiB runs, 1024 lanes) pay off once the replicas together exceed this many
-  // bytes; below it the small shape streams better (more, shorter workgroups per launch)
-  uint64_t medium_min_footprint = uint64_t(3) << 29;
+  uint32_t block = 1024;        // workgroup of launches over long tiles
+  uint32_t small_block = 256;   // ... over small tiles
+  uint32_t stream_major = 4;    // vectors per lane of the stream-major kernel for long tiles (0 = off)
+  uint64_t launch_min_bytes = 4u << 20;        // launches over small tiles: units share one up to this size
+  uint64_t long_launch_min_bytes = 64u << 20;  // launches over long tiles likewise
+  uint64_t pipeline_min_bytes = ~uint64_t(0);  // AUTO never pipelines unless told to
 };
 
 // Fork/join events order work between streams of the same device; no timing, and no system-scope
 // fence (device scope is enough: every producer and consumer is a kernel on this GPU).
 constexpr unsigned kOrderOnly = hipEventDisableTiming | hipEventDisableSystemFence;
 
+// One reduce launch: consecutive tiles of one class that belong to consecutive units of one lane.
 struct LaunchGroup {
-  uint32_t stream, first_unit;
-  Range reduce, copy;
-  bool large;  // made of large units only: large workgroups
-  bool lng;    // ... in a stream with enough of them for long launches: large tiles, stream-major kernel
+  uint32_t lane, first_unit;
+  int cls;  // kLong or kSmall
+  Range reduce;
+  uint64_t elems;  // elements per replica the launch covers
 };
 
 struct TimedLaunch {
   int kind;
   uint64_t call;
   hipEvent_t start, stop;
+};
+
+// What binding a plan to a set of gradient pointers produces on the host.
+struct Binding {
+  TileShape shape;             // the shape the tables were built with
+  std::vector<uint64_t> rows;  // (n_tensors + 1) x W base addresses
+  TileTables tt;
+  std::vector<LaunchGroup> groups[2];  // [0] staged tables, [1] direct tables
+  bool groups_stale[2] = {true, true};
+  bool groups_pipelined[2] = {false, false};
+};
+
+// Where the kernels find the tables of a binding.
+struct DeviceTables {
+  const uint64_t* rows = nullptr;
+  const ReduceTile* staged = nullptr;
+  const ReduceTile* direct = nullptr;
+  const CopyTile* copy = nullptr;
 };
 
 }  // namespace
@@ -95,11 +111,7 @@ struct caramel_plan {
   bool bound = false;
   bool has_ws = false;
   int device = -1;  // the device that was current at bind: tables, stream and events live there
-  TileShape bound_shape;        // the shape the tables were built with
-  uint32_t medium_block = 1024;  // workgroup size of launches over medium tiles
-  TileTables tt;
-  std::vector<LaunchGroup> groups[2];  // [0] staged tables, [1] direct tables
-  bool groups_stale[2] = {true, true};
+  Binding bind;
   uint64_t* d_rows = nullptr;
   ReduceTile* d_staged = nullptr;
   ReduceTile* d_direct = nullptr;
@@ -114,6 +126,8 @@ struct caramel_plan {
   std::vector<hipEvent_t> spare;
   std::vector<std::pair<uint64_t, hipEvent_t>> call_base;
   caramel_kernel_stat stats[CARAMEL_K_COUNT] = {};
+
+  DeviceTables tables() const { return DeviceTables{d_rows, d_staged, d_direct, d_copy}; }
 };
 
 namespace {
@@ -169,10 +183,11 @@ struct Timed {
   hipStream_t s;
   TimedLaunch t{};
   bool on = false;
-  Timed(caramel_plan* plan, int kind, hipStream_t stream) : p(plan), s(stream) {
+  Timed(caramel_plan* plan, int kind, hipStream_t stream, uint64_t elems = 0) : p(plan), s(stream) {
     if (!p->profiling) return;
     if (kind != CARAMEL_K_SEQUENCE) {
       p->stats[kind].launches += 1;
+      p->stats[kind].elements += elems;
       if (p->profiling < 2) return;
     }
     t.kind = kind;
@@ -190,34 +205,37 @@ struct Timed {
   }
 };
 
-int run_reduce(caramel_plan* p, bool direct, Range r, bool large, bool lng, hipStream_t s) {
+int run_reduce(caramel_plan* p, const Binding& bd, const DeviceTables& dt, bool direct, const LaunchGroup& g,
+               hipStream_t s) {
+  const Range r = g.reduce;
+  const int cls = g.cls;
   if (r.count == 0) return CARAMEL_OK;
   ReduceArgs a{};
-  a.tiles = direct ? p->d_direct : p->d_staged;
-  a.rows = p->d_rows;
+  a.tiles = direct ? dt.direct : dt.staged;
+  a.rows = dt.rows;
   a.begin = r.begin;
   a.count = r.count;
   a.world = p->host.cfg.world;
   a.bf16 = p->host.cfg.dtype == CARAMEL_BF16;
   a.nontemporal = p->opt.nontemporal != 0;
   a.tree = p->host.cfg.pattern == CARAMEL_PATTERN_HALVING_DOUBLING;
-  // by default a workgroup takes its tile in one go: vectors per lane = tile / workgroup size
-  a.block = !large ? p->opt.small_block : (lng ? p->opt.block : p->medium_block);
-  const TileShape& shape = p->bound_shape;
-  const uint32_t tile_vecs = !large ? shape.small_vecs : (lng ? shape.large_vecs : shape.medium_vecs);
+  // by default a workgroup takes a whole tile in one go: vectors per lane = tile / workgroup size
+  const bool lng = cls == kLong;
+  a.block = lng ? p->opt.block : p->opt.small_block;
+  const uint32_t tile_vecs = lng ? bd.shape.long_vecs : bd.shape.small_vecs;
   a.unroll = p->opt.unroll ? p->opt.unroll : std::max(1u, tile_vecs / a.block);
   a.stream_major = lng ? p->opt.stream_major : 0;
   a.max_grid = p->opt.max_grid;
-  Timed timer(p, CARAMEL_K_REDUCE, s);
+  Timed timer(p, lng ? CARAMEL_K_REDUCE : CARAMEL_K_REDUCE_SMALL, s, g.elems);
   HIP_TRY(launch_ring_reduce(a, s));
   return CARAMEL_OK;
 }
 
-int run_copy(caramel_plan* p, bool unpack, Range r, hipStream_t s) {
+int run_copy(caramel_plan* p, const DeviceTables& dt, bool unpack, Range r, hipStream_t s) {
   if (r.count == 0) return CARAMEL_OK;
   CopyArgs a{};
-  a.tiles = p->d_copy;
-  a.rows = p->d_rows;
+  a.tiles = dt.copy;
+  a.rows = dt.rows;
   a.begin = r.begin;
   a.count = r.count;
   a.world = p->host.cfg.world;
@@ -257,13 +275,13 @@ int join_streams(caramel_plan* p, hipStream_t user, bool pipelined) {
   return CARAMEL_OK;
 }
 
-// A launch covers consecutive units of one class (large or small) and one stream; their tiles
-// are adjacent in the tables, so a launch is one tile range.  PER_UNIT: units are added until the
-// launch covers at least the class's minimum bytes per replica.  PER_STREAM: one launch per
-// class and stream.  The order in which a stream's launches are issued does not affect results.
-// AUTO: the two-stream pipeline pays a fixed price for its fork and join (tens of microseconds
-// of cross-stream signalling), so it is used only when a call moves enough bytes to win that
-// back; smaller calls go out as one launch per stream on the caller's stream.
+// A reduce launch covers the tiles of one class (long or small) of consecutive units of one
+// stream; they are adjacent in the tables, so a launch is one tile range.  PER_UNIT: units are
+// added until the launch covers at least the class's minimum bytes per replica.  PER_STREAM: one
+// launch per class and stream.  The order in which a stream's launches are issued does not
+// affect results.  AUTO: the two-stream pipeline pays a fixed price for its fork and join (tens
+// of microseconds of cross-stream signalling), so it is used only when a call moves enough
+// bytes to win that back; smaller calls go out as one launch per class on the caller's stream.
 bool use_pipeline(const caramel_plan* p) {
   if (p->host.cfg.num_streams != 2) return false;
   if (p->opt.launch_mode != CARAMEL_LAUNCH_AUTO) return true;
@@ -272,42 +290,38 @@ bool use_pipeline(const caramel_plan* p) {
   return 2 * uint64_t(p->host.cfg.world) * elems * p->host.elem_size() >= p->opt.pipeline_min_bytes;
 }
 
-const std::vector<LaunchGroup>& launch_groups(caramel_plan* p, bool direct) {
-  std::vector<LaunchGroup>& out = p->groups[direct ? 1 : 0];
-  if (!p->groups_stale[direct ? 1 : 0]) return out;
+const std::vector<LaunchGroup>& launch_groups(const caramel_plan* p, Binding& bd, bool direct, bool pipelined) {
+  const int ti = direct ? 1 : 0;
+  std::vector<LaunchGroup>& out = bd.groups[ti];
+  if (!bd.groups_stale[ti] && bd.groups_pipelined[ti] == pipelined) return out;
   out.clear();
-  const TileTables& tt = p->tt;
-  const std::vector<Range>& unit_tiles = direct ? tt.direct_unit : tt.staged_unit;
+  const TileTables& tt = bd.tt;
+  const std::vector<UnitTiles>& unit_tiles = direct ? tt.direct_unit : tt.staged_unit;
   uint32_t mode = p->opt.launch_mode;
-  const bool pipelined = use_pipeline(p);
   if (mode == CARAMEL_LAUNCH_AUTO) mode = pipelined ? CARAMEL_LAUNCH_PER_UNIT : CARAMEL_LAUNCH_PER_STREAM;
   const uint64_t es = p->host.elem_size();
-  // Without the pipeline both plan streams run on the caller's stream: treat them as one.
+  // Without the pipeline both plan streams run on the caller's stream: treat them as one lane.
   const uint32_t lanes = pipelined ? p->host.cfg.num_streams : 1;
   for (int cls = 0; cls < 2; ++cls) {
+    const uint64_t min_bytes = cls == kLong ? p->opt.long_launch_min_bytes : p->opt.launch_min_bytes;
     for (uint32_t lane = 0; lane < lanes; ++lane) {
       LaunchGroup g{};
-      uint64_t bytes = 0, min_bytes = 0;
+      uint64_t bytes = 0;
       bool open = false;
       const size_t mine = out.size();  // launches of this class and lane start here
       for (uint32_t s = 0; s < p->host.cfg.num_streams; ++s) {
         if (pipelined && s != lane) continue;
-        const bool lng = cls == kLarge && tt.long_launches[s];
-        min_bytes = lng ? p->opt.large_launch_min_bytes : p->opt.launch_min_bytes;
-        // tiles of a long-launch stream and of another stream differ in shape: never one launch
-        if (open && g.lng != lng) {
-          out.push_back(g);
-          open = false;
-        }
-        for (uint32_t u : tt.order[cls][s]) {
+        for (uint32_t u : tt.order[s]) {
+          const UnitTiles& ut = unit_tiles[u];
+          if (ut.tiles[cls].count == 0) continue;
           if (!open) {
-            g = LaunchGroup{lane, u, Range{unit_tiles[u].begin, 0}, Range{tt.copy_unit[u].begin, 0}, cls == kLarge, lng};
+            g = LaunchGroup{lane, u, cls, Range{ut.tiles[cls].begin, 0}, 0};
             bytes = 0;
             open = true;
           }
-          g.reduce.count += unit_tiles[u].count;
-          g.copy.count += tt.copy_unit[u].count;
-          bytes += p->host.units[u].elems * es;
+          g.reduce.count += ut.tiles[cls].count;
+          g.elems += ut.elems[cls];
+          bytes += ut.elems[cls] * es;
           if (mode == CARAMEL_LAUNCH_PER_UNIT && bytes >= min_bytes) {
             out.push_back(g);
             open = false;
@@ -318,29 +332,28 @@ const std::vector<LaunchGroup>& launch_groups(caramel_plan* p, bool direct) {
         // what is left over at the end is rarely worth a launch of its own: less than half the
         // minimum joins the launch before it (its tiles follow that launch's in the table)
         LaunchGroup* prev = out.size() > mine ? &out.back() : nullptr;
-        if (prev && bytes < min_bytes / 2 && prev->lng == g.lng &&
-            prev->reduce.begin + prev->reduce.count == g.reduce.begin &&
-            prev->copy.begin + prev->copy.count == g.copy.begin) {
+        if (prev && bytes < min_bytes / 2 && prev->reduce.begin + prev->reduce.count == g.reduce.begin) {
           prev->reduce.count += g.reduce.count;
-          prev->copy.count += g.copy.count;
+          prev->elems += g.elems;
         } else {
           out.push_back(g);
         }
       }
     }
   }
-  // issue in the order of the first unit, which alternates between the streams
+  // issue in the order of the first unit, which alternates between the streams ...
   std::stable_sort(out.begin(), out.end(),
                    [](const LaunchGroup& a, const LaunchGroup& b) { return a.first_unit < b.first_unit; });
-  // ... but every stream issues its launches over small units first: a call then ends with the
-  // long, evenly sized launches over large units running on both streams, and the streams finish
-  // together (measured: VGG-16 -0.5 %, AlexNet-v2 -2.3 %, ResNet-50 -1.1 % time per call).
-  std::stable_sort(out.begin(), out.end(), [](const LaunchGroup& a, const LaunchGroup& b) { return a.large < b.large; });
-  p->groups_stale[direct ? 1 : 0] = false;
+  // ... but every stream issues its launches over small tiles first: a call then ends with the
+  // long, evenly sized launches running on both streams, and the streams finish together
+  std::stable_sort(out.begin(), out.end(), [](const LaunchGroup& a, const LaunchGroup& b) { return a.cls > b.cls; });
+  bd.groups_stale[ti] = false;
+  bd.groups_pipelined[ti] = pipelined;
   return out;
 }
 
-// Shared body of caramel_ring_reduce (reduce only, staged tables) and caramel_allreduce.
+// Shared body of caramel_ring_reduce (reduce only, staged tables) and caramel_allreduce.  In
+// staged mode every lane packs all its batch units, reduces, and unpacks them, in stream order.
 int pipeline(caramel_plan* p, hipStream_t user, bool with_copies, bool direct) {
   begin_call(p, user);
   hipStream_t lane[2] = {nullptr, nullptr};
@@ -348,17 +361,25 @@ int pipeline(caramel_plan* p, hipStream_t user, bool with_copies, bool direct) {
   int rc = fork_streams(p, user, lane, pipelined);
   if (rc) return rc;
   const bool copies = with_copies && !direct;
+  const DeviceTables dt = p->tables();
+  const TileTables& tt = p->bind.tt;
+  const uint32_t n_lanes = pipelined ? 2u : 1u;
+  // the copy tiles of a lane: of its stream, or of both streams when there is one lane
+  Range copy_of[2] = {tt.copy_stream[0], tt.copy_stream[1]};
+  if (!pipelined) copy_of[0].count = tt.copy_stream[0].count + tt.copy_stream[1].count;
   // one event pair around everything a stream does in this call
   std::unique_ptr<Timed> seq[2];
   if (p->profiling)
-    for (uint32_t s = 0; s < (pipelined ? 2u : 1u); ++s) seq[s].reset(new Timed(p, CARAMEL_K_SEQUENCE, lane[s]));
-  for (const LaunchGroup& g : launch_groups(p, direct)) {
-    hipStream_t s = lane[g.stream];
-    if (copies) rc = run_copy(p, false, g.copy, s);
-    if (!rc) rc = run_reduce(p, direct, g.reduce, g.large, g.lng, s);
-    if (!rc && copies) rc = run_copy(p, true, g.copy, s);
-    if (rc) break;
-  }
+    for (uint32_t s = 0; s < n_lanes; ++s) seq[s].reset(new Timed(p, CARAMEL_K_SEQUENCE, lane[s]));
+  if (copies)
+    for (uint32_t s = 0; s < n_lanes && !rc; ++s) rc = run_copy(p, dt, false, copy_of[s], lane[s]);
+  if (!rc)
+    for (const LaunchGroup& g : launch_groups(p, p->bind, direct, pipelined)) {
+      rc = run_reduce(p, p->bind, dt, direct, g, lane[g.lane]);
+      if (rc) break;
+    }
+  if (copies)
+    for (uint32_t s = 0; s < n_lanes && !rc; ++s) rc = run_copy(p, dt, true, copy_of[s], lane[s]);
   for (auto& q : seq) q.reset();
   // join even after a failed launch so the caller's stream stays ordered
   const int jc = join_streams(p, user, pipelined);
@@ -413,8 +434,14 @@ int caramel_net_model_fit(uint64_t bytes1, double time1, uint64_t bytes2, double
   if (bytes1 == bytes2) return fail(CARAMEL_EINVAL, "the two sizes must differ");
   if (!std::isfinite(time1) || !std::isfinite(time2)) return fail(CARAMEL_EINVAL, "times must be finite");
   const double slope = (time2 - time1) / (double(bytes2) - double(bytes1));
+  const double icpt = time1 - slope * double(bytes1);
+  if (!(slope > 0.0) || !(icpt >= 0.0))
+    return fail(CARAMEL_EINVAL,
+                "the probes (%llu B in %g, %llu B in %g) give the line %g + %g * bytes: a transfer-time model "
+                "needs a >= 0 and b > 0 (time must grow with size); measure again",
+                (unsigned long long)bytes1, time1, (unsigned long long)bytes2, time2, icpt, slope);
   *b = slope;
-  *a = time1 - slope * double(bytes1);
+  *a = icpt;
   return CARAMEL_OK;
 }
 
@@ -548,11 +575,15 @@ int caramel_plan_serialize(const caramel_plan* p, void* buf, size_t* len) {
 
 int caramel_plan_set_option(caramel_plan* p, uint32_t option, uint64_t value) {
   if (!p) return fail(CARAMEL_EINVAL, "plan is NULL");
+  auto regroup = [&] {
+    p->bind.groups_stale[0] = p->bind.groups_stale[1] = true;
+  };
+  auto is_block = [](uint64_t v) { return v == 256 || v == 512 || v == 1024; };
   switch (option) {
     case CARAMEL_OPT_LAUNCH_MODE:
       if (value > CARAMEL_LAUNCH_AUTO) return fail(CARAMEL_EINVAL, "unknown launch mode");
       p->opt.launch_mode = uint32_t(value);
-      p->groups_stale[0] = p->groups_stale[1] = true;
+      regroup();
       return CARAMEL_OK;
     case CARAMEL_OPT_BATCH_PATH:
       if (value > CARAMEL_BATCH_DIRECT) return fail(CARAMEL_EINVAL, "unknown batch path");
@@ -560,41 +591,30 @@ int caramel_plan_set_option(caramel_plan* p, uint32_t option, uint64_t value) {
       return CARAMEL_OK;
     case CARAMEL_OPT_TILE_VECS:
       if (value < 64 || value > (1u << 20)) return fail(CARAMEL_EINVAL, "tile_vecs must be in [64, 2^20]");
-      p->opt.shape.large_vecs = uint32_t(value);
+      p->opt.shape.long_vecs = uint32_t(value);
       return CARAMEL_OK;
     case CARAMEL_OPT_SMALL_TILE_VECS:
       if (value < 64 || value > (1u << 20)) return fail(CARAMEL_EINVAL, "tile_vecs must be in [64, 2^20]");
       p->opt.shape.small_vecs = uint32_t(value);
       return CARAMEL_OK;
     case CARAMEL_OPT_SMALL_BLOCK:
-      if (value != 256 && value != 512 && value != 1024) return fail(CARAMEL_EINVAL, "block must be 256, 512 or 1024");
+      if (!is_block(value)) return fail(CARAMEL_EINVAL, "block must be 256, 512 or 1024");
       p->opt.small_block = uint32_t(value);
       return CARAMEL_OK;
-    case CARAMEL_OPT_LARGE_LAUNCH_MIN_BYTES:
-      p->opt.large_launch_min_bytes = value;
-      p->groups_stale[0] = p->groups_stale[1] = true;
+    case CARAMEL_OPT_LONG_LAUNCH_MIN_BYTES:
+      p->opt.long_launch_min_bytes = value;
+      regroup();
       return CARAMEL_OK;
     case CARAMEL_OPT_STREAM_MAJOR:
       if (value != 0 && value != 2 && value != 4) return fail(CARAMEL_EINVAL, "stream_major must be 0, 2 or 4");
       p->opt.stream_major = uint32_t(value);
       return CARAMEL_OK;
-    case CARAMEL_OPT_MEDIUM_TILE_VECS:
-      if (value < 64 || value > (1u << 20)) return fail(CARAMEL_EINVAL, "tile_vecs must be in [64, 2^20]");
-      p->opt.shape.medium_vecs = uint32_t(value);
-      return CARAMEL_OK;
     case CARAMEL_OPT_ALIGN_TILES:
       if (value > 3) return fail(CARAMEL_EINVAL, "align_tiles must be 0..3");
       p->opt.shape.align_tiles = uint32_t(value);
       return CARAMEL_OK;
-    case CARAMEL_OPT_MEDIUM_MIN_FOOTPRINT:
-      p->opt.medium_min_footprint = value;
-      return CARAMEL_OK;
-    case CARAMEL_OPT_LONG_LAUNCH_BYTES:
-      p->opt.shape.long_bytes = value;
-      return CARAMEL_OK;
-    case CARAMEL_OPT_LARGE_UNIT_BYTES:
-      p->opt.shape.large_bytes = value;
-      p->groups_stale[0] = p->groups_stale[1] = true;
+    case CARAMEL_OPT_LONG_RUN_BYTES:
+      p->opt.shape.long_run_bytes = value;
       return CARAMEL_OK;
     case CARAMEL_OPT_MAX_GRID:
       if (value > 0x7FFFFFFFu) return fail(CARAMEL_EINVAL, "max_grid too large");
@@ -609,14 +629,14 @@ int caramel_plan_set_option(caramel_plan* p, uint32_t option, uint64_t value) {
       return CARAMEL_OK;
     case CARAMEL_OPT_LAUNCH_MIN_BYTES:
       p->opt.launch_min_bytes = value;
-      p->groups_stale[0] = p->groups_stale[1] = true;
+      regroup();
       return CARAMEL_OK;
     case CARAMEL_OPT_PIPELINE_MIN_BYTES:
       p->opt.pipeline_min_bytes = value;
-      p->groups_stale[0] = p->groups_stale[1] = true;
+      regroup();
       return CARAMEL_OK;
     case CARAMEL_OPT_BLOCK:
-      if (value != 256 && value != 512 && value != 1024) return fail(CARAMEL_EINVAL, "block must be 256, 512 or 1024");
+      if (!is_block(value)) return fail(CARAMEL_EINVAL, "block must be 256, 512 or 1024");
       p->opt.block = uint32_t(value);
       return CARAMEL_OK;
     default:
@@ -635,13 +655,11 @@ int caramel_bind(caramel_plan* p, void* const* grads, void* fused_ws) {
 }  // extern "C"
 
 namespace {
-int bind_plan(caramel_plan* p, void* const* grads, void* fused_ws) {
-  if (!p || !grads) return fail(CARAMEL_EINVAL, "NULL argument");
-  const HostPlan& h = p->host;
+// Argument checks of a binding; on success `rows` holds the (n_tensors + 1) x W base addresses.
+int check_pointers(const HostPlan& h, void* const* grads, void* fused_ws, std::vector<uint64_t>& rows) {
   const uint32_t W = h.cfg.world;
   const size_t n = h.tensor_elems.size();
   const uint64_t es = h.elem_size();
-  // argument checks first: nothing is touched on the device if they fail
   struct Span {
     uint64_t lo, hi;
   };
@@ -662,6 +680,27 @@ int bind_plan(caramel_plan* p, void* const* grads, void* fused_ws) {
   std::sort(spans.begin(), spans.end(), [](const Span& x, const Span& y) { return x.lo < y.lo; });
   for (size_t i = 1; i < spans.size(); ++i)
     if (spans[i].lo < spans[i - 1].hi) return fail(CARAMEL_EINVAL, "gradient / workspace buffers overlap");
+  rows.assign((n + 1) * W, 0);
+  for (uint32_t w = 0; w < W; ++w) {
+    for (size_t t = 0; t < n; ++t) rows[t * W + w] = reinterpret_cast<uint64_t>(grads[w * n + t]);
+    rows[n * W + w] = fused_ws ? reinterpret_cast<uint64_t>(fused_ws) + uint64_t(w) * h.fused_elems * es : 0;
+  }
+  return CARAMEL_OK;
+}
+
+void fill_binding(const caramel_plan* p, std::vector<uint64_t>&& rows, Binding& bd) {
+  bd.shape = p->opt.shape;
+  bd.rows = std::move(rows);
+  build_tiles(p->host, bd.shape, bd.tt, bd.rows.data());
+  bd.groups_stale[0] = bd.groups_stale[1] = true;
+}
+
+int bind_plan(caramel_plan* p, void* const* grads, void* fused_ws) {
+  if (!p || !grads) return fail(CARAMEL_EINVAL, "NULL argument");
+  const HostPlan& h = p->host;
+  // argument checks first: nothing is touched on the device if they fail
+  std::vector<uint64_t> rows;
+  if (int rc = check_pointers(h, grads, fused_ws, rows)) return rc;
 
   // a plan stays on the device it was first bound on: its stream and events live there
   int dev = -1;
@@ -673,34 +712,25 @@ int bind_plan(caramel_plan* p, void* const* grads, void* fused_ws) {
   release_device(p);
   p->device = dev;
 
-  std::vector<uint64_t> rows((n + 1) * W, 0);
-  for (uint32_t w = 0; w < W; ++w) {
-    for (size_t t = 0; t < n; ++t) rows[t * W + w] = reinterpret_cast<uint64_t>(grads[w * n + t]);
-    rows[n * W + w] = fused_ws ? reinterpret_cast<uint64_t>(fused_ws) + uint64_t(w) * h.fused_elems * es : 0;
-  }
-  // replicas that are small in total: medium tiles take the small shape
-  p->bound_shape = p->opt.shape;
-  p->medium_block = p->opt.block;
-  uint64_t footprint = 0;
-  for (uint64_t e : h.tensor_elems) footprint += e * es * W;
-  if (footprint < p->opt.medium_min_footprint) {
-    p->bound_shape.medium_vecs = p->opt.shape.small_vecs;
-    p->medium_block = p->opt.small_block;
-  }
-  build_tiles(h, p->bound_shape, p->tt, rows.data());
-  p->groups_stale[0] = p->groups_stale[1] = true;
-  int rc = upload(rows, &p->d_rows);
-  if (!rc) rc = upload(p->tt.direct, &p->d_direct);
-  if (!rc && fused_ws) rc = upload(p->tt.staged, &p->d_staged);
-  if (!rc && fused_ws) rc = upload(p->tt.copy, &p->d_copy);
+  fill_binding(p, std::move(rows), p->bind);
+  int rc = upload(p->bind.rows, &p->d_rows);
+  if (!rc) rc = upload(p->bind.tt.direct, &p->d_direct);
+  if (!rc && fused_ws) rc = upload(p->bind.tt.staged, &p->d_staged);
+  if (!rc && fused_ws) rc = upload(p->bind.tt.copy, &p->d_copy);
   if (rc) {
     release_device(p);
     return rc;
   }
-  if (h.cfg.num_streams > 1 && !p->streams[1]) {
-    HIP_TRY(hipStreamCreateWithFlags(&p->streams[1], hipStreamNonBlocking));
-    HIP_TRY(hipEventCreateWithFlags(&p->ev_join[1], kOrderOnly));
-    HIP_TRY(hipEventCreateWithFlags(&p->ev_fork, kOrderOnly));
+  if (h.cfg.num_streams > 1) {
+    // each handle under its own check: a plan whose earlier bind failed half-way is completed here
+    hipError_t e = hipSuccess;
+    if (!p->streams[1]) e = hipStreamCreateWithFlags(&p->streams[1], hipStreamNonBlocking);
+    if (e == hipSuccess && !p->ev_join[1]) e = hipEventCreateWithFlags(&p->ev_join[1], kOrderOnly);
+    if (e == hipSuccess && !p->ev_fork) e = hipEventCreateWithFlags(&p->ev_fork, kOrderOnly);
+    if (e != hipSuccess) {
+      release_device(p);  // the tables go too: the plan stays unbound
+      return fail(CARAMEL_EHIP, "creating the internal stream and its events: %s", hipGetErrorString(e));
+    }
   }
   p->has_ws = fused_ws != nullptr;
   p->bound = true;
@@ -714,8 +744,8 @@ int caramel_pack(caramel_plan* p, void* stream) {
   return guarded([&]() -> int {
     if (int rc = need_bound(p, true)) return rc;
     begin_call(p, hipStream_t(stream));
-    Range all{0, uint32_t(p->tt.copy.size())};
-    return run_copy(p, false, all, hipStream_t(stream));
+    Range all{0, uint32_t(p->bind.tt.copy.size())};
+    return run_copy(p, p->tables(), false, all, hipStream_t(stream));
   });
 }
 
@@ -723,8 +753,8 @@ int caramel_unpack(caramel_plan* p, void* stream) {
   return guarded([&]() -> int {
     if (int rc = need_bound(p, true)) return rc;
     begin_call(p, hipStream_t(stream));
-    Range all{0, uint32_t(p->tt.copy.size())};
-    return run_copy(p, true, all, hipStream_t(stream));
+    Range all{0, uint32_t(p->bind.tt.copy.size())};
+    return run_copy(p, p->tables(), true, all, hipStream_t(stream));
   });
 }
 

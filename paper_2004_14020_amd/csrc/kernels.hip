@@ -76,6 +76,11 @@ struct Chain {
       a = a + bits_to_f32(x);
     }
   }
+  // this partial sum + another one
+  __device__ __forceinline__ void merge(const Chain& o) {
+    a = a + o.a;
+    if constexpr (BF16) b = b + o.b;
+  }
   __device__ __forceinline__ u32x4 finish(float inv_w) {
     if constexpr (BF16) {
       const f32x4 ya = a * inv_w, yb = b * inv_w;
@@ -201,6 +206,53 @@ k_ring_reduce(const ReduceTile* __restrict__ tiles, const uint64_t* __restrict__
   }
 }
 
+// One stream-major pass over U vectors of this lane (B apart, starting at v): the chain is walked
+// one worker at a time, with the next worker's U loads in flight while the current ones are added.
+// RAGGED: the last of the U vectors may lie at or beyond nvec; such a lane reads the tile's last
+// vector instead (no divergence among the loads) and stores nothing for it.
+template <int W, int U, bool BF16, bool NT, bool RAGGED>
+__device__ __forceinline__ void sm_walk(const gvec_ptr (&p)[W], uint32_t v, uint32_t B, uint32_t nvec, float inv_w) {
+  u32x4 cur[U], nxt[U];
+  Chain<BF16> acc[U];
+  const bool last_ok = !RAGGED || v + (U - 1) * B < nvec;
+  auto off = [&](int u) -> uint32_t {
+    if (RAGGED && u == U - 1) return (last_ok ? v + (U - 1) * B : nvec - 1) * 16u;
+    return (v + u * B) * 16u;
+  };
+#pragma unroll
+  for (int u = 0; u < U; ++u) cur[u] = ld<NT>(at(p[0], off(u)));
+#pragma unroll
+  for (int k = 1; k < W; ++k) {
+#pragma unroll
+    for (int u = 0; u < U; ++u) nxt[u] = ld<NT>(at(p[k], off(u)));
+    __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+      if (k == 1) acc[u].start(cur[u]);
+      else acc[u].add(cur[u]);
+      cur[u] = nxt[u];
+    }
+    __builtin_amdgcn_sched_barrier(0);
+  }
+  u32x4 y[U];
+#pragma unroll
+  for (int u = 0; u < U; ++u) {
+    acc[u].add(cur[u]);
+    y[u] = acc[u].finish(inv_w);
+  }
+  constexpr int SURE = RAGGED ? U - 1 : U;  // vectors that are stored by every lane
+#pragma unroll
+  for (int k = 0; k < W; ++k)
+#pragma unroll
+    for (int u = 0; u < SURE; ++u) st<NT>(at(p[k], off(u)), y[u]);
+  if constexpr (RAGGED) {
+    if (last_ok) {
+#pragma unroll
+      for (int k = 0; k < W; ++k) st<NT>(at(p[k], off(U - 1)), y[U - 1]);
+    }
+  }
+}
+
 // Stream-major variant for large tiles (chain orders only).  A lane handles U vectors, but
 // instead of fetching all W workers' values at once it walks the chain one worker at a time,
 // with the next worker's U loads in flight while the current ones are added.  A 1024-lane
@@ -223,7 +275,8 @@ k_ring_reduce_sm(const ReduceTile* __restrict__ tiles, const uint64_t* __restric
     const uint32_t nvec = tl.n_elems / VE;
     const uint32_t B = blockDim.x;
     uint32_t v = threadIdx.x;
-    for (; v + (U - 1) * B < nvec; v += U * B) {
+    const uint32_t whole = nvec / (U * B) * (U * B);  // the same for all lanes
+    for (; v < whole; v += U * B) {
       u32x4 cur[U], nxt[U];
       Chain<BF16> acc[U];
 #pragma unroll
@@ -252,14 +305,25 @@ k_ring_reduce_sm(const ReduceTile* __restrict__ tiles, const uint64_t* __restric
 #pragma unroll
         for (int u = 0; u < U; ++u) st<NT>(at(p[k], (v + u * B) * 16u), y[u]);
     }
-    for (; v < nvec; v += B) {
-      u32x4 x[W];
+    // what is left (fewer than U*B vectors: up to U rows of B lanes, the last row possibly
+    // ragged) is walked the same way in one go
+    const uint32_t rows_left = (nvec - whole + B - 1) / B;
+    if (rows_left == 1) {
+      // at most one vector per lane: nothing to walk, fetch all workers' values at once
+      if (v < nvec) {
+        u32x4 x[W];
 #pragma unroll
-      for (int k = 0; k < W; ++k) x[k] = ld<NT>(at(p[k], v * 16u));
-      __builtin_amdgcn_sched_barrier(0);
-      const u32x4 y = combine<W, BF16, false>(x, inv_w);
+        for (int k = 0; k < W; ++k) x[k] = ld<NT>(at(p[k], v * 16u));
+        __builtin_amdgcn_sched_barrier(0);
+        const u32x4 y = combine<W, BF16, false>(x, inv_w);
 #pragma unroll
-      for (int k = 0; k < W; ++k) st<NT>(at(p[k], v * 16u), y);
+        for (int k = 0; k < W; ++k) st<NT>(at(p[k], v * 16u), y);
+      }
+    }
+    if (rows_left == 2) sm_walk<W, 2, BF16, NT, true>(p, v, B, nvec, inv_w);
+    if constexpr (U >= 4) {
+      if (rows_left == 3) sm_walk<W, 3, BF16, NT, true>(p, v, B, nvec, inv_w);
+      if (rows_left == 4) sm_walk<W, 4, BF16, NT, true>(p, v, B, nvec, inv_w);
     }
     const uint32_t rem = tl.n_elems - nvec * VE;
     if (threadIdx.x < rem) {
@@ -359,6 +423,93 @@ k_ring_reduce_any(const ReduceTile* __restrict__ tiles, const uint64_t* __restri
   }
 }
 
+// Balanced pairwise tree (halving-doubling order) for W = 32 or 64.  The workers are taken eight
+// at a time: their eight vectors are added as a three-level tree, and the partial sums of the
+// blocks are merged the way a binary counter carries (block j closes as many levels as j + 1 has
+// trailing zeros), which is the same tree  ((x0+x1)+(x2+x3)) + ...  up to its root.
+template <bool BF16, bool NT>
+__global__ void __launch_bounds__(kMaxBlock)
+k_ring_reduce_tree_any(const ReduceTile* __restrict__ tiles, const uint64_t* __restrict__ rows, uint32_t begin,
+                       uint32_t count, uint32_t W, float inv_w) {
+  constexpr uint32_t VE = BF16 ? 8 : 4;
+  constexpr int kBlk = 8;       // workers per block
+  constexpr int kMaxBlocks = 8;  // W <= 64
+  for (uint32_t ti = blockIdx.x; ti < count; ti += gridDim.x) {
+    const ReduceTile tl = tiles[begin + ti];
+    const uint64_t* row = rows + size_t(tl.row) * W;
+    const uint32_t nvec = tl.n_elems / VE;
+    const uint32_t n_blocks = W / kBlk;
+    for (uint32_t v = threadIdx.x; v < nvec; v += blockDim.x) {
+      Chain<BF16> part[4];  // open partial sums of 8, 16, 32 workers (and the root of 64)
+      u32x4 y = {0u, 0u, 0u, 0u};
+#pragma unroll
+      for (int j = 0; j < kMaxBlocks; ++j) {
+        if (uint32_t(j) < n_blocks) {
+          u32x4 x[kBlk];
+#pragma unroll
+          for (int i = 0; i < kBlk; ++i)
+            x[i] = ld<NT>(at(reinterpret_cast<gvec_ptr>(row[j * kBlk + i]) + tl.vec_off, v * 16u));
+          __builtin_amdgcn_sched_barrier(0);
+          Chain<BF16> t[kBlk];
+#pragma unroll
+          for (int i = 0; i < kBlk; ++i) t[i].start(x[i]);
+#pragma unroll
+          for (int s = 1; s < kBlk; s *= 2)
+#pragma unroll
+            for (int i = 0; i + s < kBlk; i += 2 * s) t[i].merge(t[i + s]);
+          // carry: j + 1 = ...1000 closes one level per trailing zero
+          int lvl = 0;
+#pragma unroll
+          for (int m = j + 1; (m & 1) == 0; m >>= 1) {
+            part[lvl].merge(t[0]);
+            t[0] = part[lvl];
+            ++lvl;
+          }
+          part[lvl] = t[0];
+          if (uint32_t(j) + 1 == n_blocks) y = t[0].finish(inv_w);
+        }
+      }
+      for (uint32_t k = 0; k < W; ++k) st<NT>(at(reinterpret_cast<gvec_ptr>(row[k]) + tl.vec_off, v * 16u), y);
+    }
+    const uint32_t rem = tl.n_elems - nvec * VE;
+    if (threadIdx.x < rem) {
+      // ragged end of a tensor, one element per lane: the same tree on scalars
+      const size_t e = size_t(tl.vec_off) * VE + nvec * VE + threadIdx.x;
+      float part[4];
+      float y = 0.f;
+#pragma unroll
+      for (int j = 0; j < kMaxBlocks; ++j) {
+        if (uint32_t(j) < n_blocks) {
+          float t[kBlk];
+#pragma unroll
+          for (int i = 0; i < kBlk; ++i) {
+            if constexpr (BF16) t[i] = widen(reinterpret_cast<gu16_ptr>(row[j * kBlk + i])[e]);
+            else t[i] = reinterpret_cast<gf32_ptr>(row[j * kBlk + i])[e];
+          }
+#pragma unroll
+          for (int s = 1; s < kBlk; s *= 2)
+#pragma unroll
+            for (int i = 0; i + s < kBlk; i += 2 * s) t[i] = t[i] + t[i + s];
+          int lvl = 0;
+#pragma unroll
+          for (int m = j + 1; (m & 1) == 0; m >>= 1) {
+            t[0] = part[lvl] + t[0];
+            ++lvl;
+          }
+          part[lvl] = t[0];
+          if (uint32_t(j) + 1 == n_blocks) y = t[0] * inv_w;
+        }
+      }
+      if constexpr (BF16) {
+        const uint16_t o = uint16_t(bf16_rne(y));
+        for (uint32_t k = 0; k < W; ++k) reinterpret_cast<gu16_ptr>(row[k])[e] = o;
+      } else {
+        for (uint32_t k = 0; k < W; ++k) reinterpret_cast<gf32_ptr>(row[k])[e] = y;
+      }
+    }
+  }
+}
+
 // ------------------------------------------------------------------------------------------
 // pack / unpack: one wavefront per copy tile, grid.y = worker.
 template <typename E, bool UNPACK>
@@ -452,8 +603,18 @@ hipError_t launch_ring_reduce(const ReduceArgs& a, hipStream_t s) {
     case 16: return launch_u<16>(a, grid, inv_w, s);
     default: break;
   }
-  // the loop kernel adds as a chain; a tree over one worker is the same thing
-  if (a.tree && a.world != 1) return hipErrorInvalidValue;
+  if (a.tree && a.world != 1) {  // a tree over one worker is the chain
+    if (a.world != 32 && a.world != 64) return hipErrorInvalidValue;
+#define CARAMEL_TREE(BF, NT) \
+  hipLaunchKernelGGL((k_ring_reduce_tree_any<BF, NT>), grid, dim3(a.block), 0, s, a.tiles, a.rows, a.begin, a.count, a.world, inv_w)
+    if (a.bf16) {
+      if (a.nontemporal) CARAMEL_TREE(true, true); else CARAMEL_TREE(true, false);
+    } else {
+      if (a.nontemporal) CARAMEL_TREE(false, true); else CARAMEL_TREE(false, false);
+    }
+#undef CARAMEL_TREE
+    return hipGetLastError();
+  }
 #define CARAMEL_ANY(BF, NT) \
   hipLaunchKernelGGL((k_ring_reduce_any<BF, NT, 4>), grid, dim3(a.block), 0, s, a.tiles, a.rows, a.begin, a.count, a.world, inv_w)
   if (a.bf16) {

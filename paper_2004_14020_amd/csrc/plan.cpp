@@ -140,9 +140,7 @@ int build_host_plan(const caramel_config& cfg, const uint64_t* elems, uint32_t n
   if (cfg.pattern > CARAMEL_PATTERN_SHUFFLE) return bad("unknown pattern");
   if (cfg.reserved != 0) return bad("reserved field must be 0");
   if (cfg.pattern == CARAMEL_PATTERN_HALVING_DOUBLING) {
-    const uint32_t w = cfg.world;
-    if (!(w == 1 || w == 2 || w == 4 || w == 8 || w == 16))
-      return bad("halving-doubling needs a world of 1, 2, 4, 8 or 16");
+    if (cfg.world & (cfg.world - 1)) return bad("halving-doubling needs a power-of-two world");
   }
   const uint64_t es = cfg.dtype == CARAMEL_F32 ? 4 : 2;
   // 32-bit offsets in units of 16 bytes address at most 64 GiB inside one tensor

@@ -33,41 +33,44 @@ struct Range {
   uint32_t begin = 0, count = 0;
 };
 
+// A run is a maximal piece of one tensor (or of the fused buffer) inside one ring segment of
+// one unit: a chunk unit has one run per segment, a batch unit addressed through its members
+// one per member and segment.  Long runs are cut into long tiles, for 1024-lane workgroups that
+// walk the replicas one after the other; the rest into small tiles, for 256-lane workgroups
+// that fetch all replicas at once.
 struct TileShape {
-  uint32_t large_vecs = 4096;        // vectors per reduce tile of a large chunk unit (long launches)
-  uint32_t medium_vecs = 1024;       // ... when a stream has too few large units for long launches
-  uint32_t small_vecs = 256;         // ... of every other unit
-  uint64_t large_bytes = 4u << 20;   // a chunk unit of at least this many bytes per replica is "large"
-  uint64_t long_bytes = 64u << 20;   // a stream whose large units total at least this much gets long launches
-  uint32_t copy_vecs = 512;          // vectors per copy tile
-  uint32_t align_tiles = 1;          // bit 0: small tiles, bit 1: medium tiles start on multiples of their size in memory where possible
+  uint32_t long_vecs = 4096;           // vectors per long tile (64 KiB per replica)
+  uint32_t small_vecs = 256;           // vectors per small tile
+  uint64_t long_run_bytes = 16u << 10;  // a run of at least this many bytes per replica is long
+  uint32_t copy_vecs = 512;            // vectors per copy tile
+  // Where every replica of a run has the same address modulo the tile size, the first tile of
+  // the run is shortened so that all later ones start on multiples of the tile size in memory
+  // (bit 0: small tiles, bit 1: long tiles).
+  uint32_t align_tiles = 3;
 };
 
-// A unit whose tiles have the large shape: long uniform runs, worth 1024-lane workgroups.
-// Batch units are cut at member boundaries into many short runs and get the small shape.
-inline bool is_large_unit(const HostPlan& p, uint32_t unit, const TileShape& ts) {
-  const caramel_unit& u = p.units[unit];
-  return u.kind == CARAMEL_KIND_CHUNK && u.elems * p.elem_size() >= ts.large_bytes;
-}
+enum { kLong = 0, kSmall = 1 };
 
-enum { kLarge = 0, kSmall = 1 };
+struct UnitTiles {
+  Range tiles[2];                // [class] range in the table
+  uint64_t elems[2] = {0, 0};    // [class] elements covered
+};
 
 struct TileTables {
+  // Both reduce tables are ordered class by class, stream by stream, unit by unit: the long
+  // tiles of the units of stream 0, of stream 1, then the small tiles likewise.  So the tiles of
+  // one class of consecutive units of a stream are adjacent.
   std::vector<ReduceTile> staged;  // batch units on the fused row, chunk units on tensor rows
   std::vector<ReduceTile> direct;  // batch units addressed through their member tensors
-  std::vector<CopyTile> copy;
-  // Units appear in the tables class by class, stream by stream: the large units of stream 0,
-  // of stream 1, then the small units of stream 0, of stream 1 -- each in unit order.  So the
-  // tiles of consecutive units of one class and stream are adjacent, and so are all tiles of
-  // one class.
-  std::vector<uint32_t> order[2][2];  // [class][stream] -> unit indices
-  bool long_launches[2] = {false, false};  // per stream: large units use large_vecs tiles (else medium_vecs)
-  std::vector<Range> staged_unit, direct_unit, copy_unit;  // tile range of every unit
+  std::vector<CopyTile> copy;      // stream by stream, unit by unit
+  std::vector<uint32_t> order[2];  // [stream] -> its units, in plan order
+  std::vector<UnitTiles> staged_unit, direct_unit;
+  std::vector<Range> copy_unit;
+  Range copy_stream[2];            // copy tiles of all batch units of a stream
 };
 
-// `row0_addr`, if given, holds (n_tensors x W) base addresses, tensor-major: large tiles are used
-// for a stream only if every large unit of it starts on a multiple of the large tile size in
-// every replica (the stream-major kernel is markedly slower on misaligned runs).
+// `row_addr`, if given, holds (n_tensors + 1) x W base addresses, row-major (the last row is
+// the fused workspace; zeros if there is none): needed to cut tiles on aligned blocks.
 void build_tiles(const HostPlan& p, const TileShape& ts, TileTables& out, const uint64_t* row_addr = nullptr);
 
 }  // namespace caramel

@@ -14,7 +14,7 @@ import time
 
 import torch
 
-from . import (LAUNCH_PER_UNIT, OPT_LAUNCH_MIN_BYTES, OPT_LAUNCH_MODE, SPLIT_ADAPTIVE, SPLIT_FIXED, SPLIT_NONE, Plan)
+from . import (LAUNCH_PER_UNIT, OPT_LAUNCH_MIN_BYTES, OPT_LAUNCH_MODE, OPT_LONG_LAUNCH_MIN_BYTES, SPLIT_ADAPTIVE, SPLIT_FIXED, SPLIT_NONE, Plan)
 from .device import Replicas
 
 
@@ -55,10 +55,12 @@ def main() -> None:
             plan = Plan(W, [n], split_mode=mode, split_bytes=piece if depth > 1 else 0, num_streams=2)
             plan.set_option(OPT_LAUNCH_MODE, LAUNCH_PER_UNIT)
             plan.set_option(OPT_LAUNCH_MIN_BYTES, 0)
+            plan.set_option(OPT_LONG_LAUNCH_MIN_BYTES, 0)
             row.append(time_plan(plan, [n], args.steps))
         plan = Plan(W, [n], split_mode=SPLIT_ADAPTIVE, split_bytes=args.threshold_bytes, max_depth=8, num_streams=2)
         plan.set_option(OPT_LAUNCH_MODE, LAUNCH_PER_UNIT)
         plan.set_option(OPT_LAUNCH_MIN_BYTES, 0)
+        plan.set_option(OPT_LONG_LAUNCH_MIN_BYTES, 0)
         adaptive_depth = plan.counts()[0]
         row.append(time_plan(plan, [n], args.steps))
         best = min(row)

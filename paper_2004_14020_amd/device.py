@@ -60,12 +60,14 @@ class Replicas:
         self.fused: Optional[torch.Tensor] = None
         if with_workspace and fe > 0:
             self.fused = torch.empty(self.world * fe * self.es, dtype=torch.uint8, device=self.device)
-        ptrs = [[a.data_ptr() + o for o in offs] for a in self.arenas]
-        plan.bind(ptrs, self.fused.data_ptr() if self.fused is not None else None)
+        plan.bind(self.pointers(), self.fused.data_ptr() if self.fused is not None else None)
+
+    def pointers(self) -> List[List[int]]:
+        """Device address of every tensor of every replica, [worker][tensor]."""
+        return [[a.data_ptr() + o for o in self.offsets] for a in self.arenas]
 
     def rebind(self) -> None:
-        ptrs = [[a.data_ptr() + o for o in self.offsets] for a in self.arenas]
-        self.plan.bind(ptrs, self.fused.data_ptr() if self.fused is not None else None)
+        self.plan.bind(self.pointers(), self.fused.data_ptr() if self.fused is not None else None)
 
     def tensor(self, w: int, t: int) -> torch.Tensor:
         o, n = self.offsets[t], self.elems[t]

@@ -27,7 +27,7 @@ static int fails = 0;
   } while (0)
 
 static void check_case(const caramel_config& cfg, const std::vector<uint64_t>& elems, uint32_t tile_vecs,
-                       uint32_t small_vecs, uint64_t large_bytes, uint32_t copy_vecs, uint64_t addr_seed) {
+                       uint32_t small_vecs, uint64_t long_run_bytes, uint32_t copy_vecs, uint64_t addr_seed) {
   HostPlan p;
   std::string why;
   const int rc = build_host_plan(cfg, elems.data(), uint32_t(elems.size()), nullptr, 0.0, 0.0, p, why);
@@ -35,11 +35,9 @@ static void check_case(const caramel_config& cfg, const std::vector<uint64_t>& e
   if (rc != CARAMEL_OK) return;
   TileTables tt;
   TileShape shape;
-  shape.large_vecs = tile_vecs;
+  shape.long_vecs = tile_vecs;
   shape.small_vecs = small_vecs;
-  shape.large_bytes = large_bytes;
-  shape.long_bytes = (large_bytes % 3 == 0) ? 0 : 200000;
-  shape.medium_vecs = 128;
+  shape.long_run_bytes = long_run_bytes;
   shape.copy_vecs = copy_vecs;
   shape.align_tiles = uint32_t(addr_seed >> 8) & 3u;
   // addr_seed 0: no addresses (tiles start where runs start).  Otherwise made-up base addresses,
@@ -63,69 +61,101 @@ static void check_case(const caramel_config& cfg, const std::vector<uint64_t>& e
 
   for (int table = 0; table < 2; ++table) {
     const std::vector<ReduceTile>& tiles = table ? tt.direct : tt.staged;
-    const std::vector<Range>& per_unit = table ? tt.direct_unit : tt.staged_unit;
+    const std::vector<UnitTiles>& per_unit = table ? tt.direct_unit : tt.staged_unit;
     // coverage counters per row
     std::map<uint32_t, std::vector<uint8_t>> seen;
     uint64_t total_tiles = 0;
     for (uint32_t u = 0; u < p.units.size(); ++u) {
       const caramel_unit& un = p.units[u];
       const uint64_t* seg = p.segments(u);
-      const Range r = per_unit[u];
-      CHECK(uint64_t(r.begin) + r.count <= tiles.size());
-      total_tiles += r.count;
-      uint32_t prev_row = ~0u, prev_seg = ~0u;
-      uint64_t prev_end = ~0ull;
-      for (uint32_t i = r.begin; i < r.begin + r.count; ++i) {
-        const ReduceTile& t = tiles[i];
-        CHECK(t.n_elems > 0 && t.n_elems <= uint64_t(!is_large_unit(p, u, shape) ? small_vecs : (tt.long_launches[un.stream] ? tile_vecs : shape.medium_vecs)) * ve);
-        CHECK(t.first < W);
-        CHECK(t.row <= fused_row);
-        const uint64_t e0 = uint64_t(t.vec_off) * ve, e1 = e0 + t.n_elems;
-        CHECK(e1 <= row_elems(t.row));
-        // ragged only at the very end of a tensor row (the fused row is whole granules)
-        if (t.n_elems % ve) CHECK(t.row != fused_row && e1 == elems[t.row]);
-        // position inside the unit -> segment -> first worker
-        uint64_t unit_pos = ~0ull;
-        if (un.kind == CARAMEL_KIND_CHUNK) {
-          const caramel_entry& e = p.entries[un.first_entry];
-          CHECK(t.row == e.tensor && e0 >= e.tensor_off && e1 <= e.tensor_off + e.elems);
-          unit_pos = e0 - e.tensor_off;
-        } else if (t.row == fused_row) {
-          CHECK(table == 0 && e0 >= un.fused_off && e1 <= un.fused_off + un.elems);
-          unit_pos = e0 - un.fused_off;
-        } else {
-          CHECK(table == 1);
-          bool found = false;
-          for (uint32_t k = 0; k < un.n_entries; ++k) {
-            const caramel_entry& e = p.entries[un.first_entry + k];
-            if (e.tensor == t.row) {
-              CHECK(e0 >= e.tensor_off && e1 <= e.tensor_off + e.elems);
-              unit_pos = e.unit_off + (e0 - e.tensor_off);
-              found = true;
+      uint64_t covered[2] = {0, 0};
+      for (int cls = 0; cls < 2; ++cls) {
+        const Range r = per_unit[u].tiles[cls];
+        const uint64_t cap = uint64_t(cls == kLong ? tile_vecs : small_vecs);
+        CHECK(uint64_t(r.begin) + r.count <= tiles.size());
+        total_tiles += r.count;
+        uint32_t prev_row = ~0u, prev_seg = ~0u;
+        uint64_t prev_end = ~0ull;
+        // length of the run (same row, same segment, contiguous) a tile belongs to
+        auto run_len = [&](uint32_t i) {
+          auto seg_of = [&](const ReduceTile& t) { return t.first; };
+          uint32_t lo = i, hi = i;
+          while (lo > r.begin && tiles[lo - 1].row == tiles[lo].row && seg_of(tiles[lo - 1]) == seg_of(tiles[lo]) &&
+                 uint64_t(tiles[lo - 1].vec_off) * ve + tiles[lo - 1].n_elems == uint64_t(tiles[lo].vec_off) * ve)
+            --lo;
+          while (hi + 1 < r.begin + r.count && tiles[hi + 1].row == tiles[hi].row && seg_of(tiles[hi + 1]) == seg_of(tiles[hi]) &&
+                 uint64_t(tiles[hi].vec_off) * ve + tiles[hi].n_elems == uint64_t(tiles[hi + 1].vec_off) * ve)
+            ++hi;
+          uint64_t n = 0;
+          for (uint32_t k = lo; k <= hi; ++k) n += tiles[k].n_elems;
+          return n;
+        };
+        for (uint32_t i = r.begin; i < r.begin + r.count; ++i) {
+          const ReduceTile& t = tiles[i];
+          CHECK(t.n_elems > 0 && t.n_elems <= cap * ve);
+          CHECK(t.first < W);
+          CHECK(t.row <= fused_row);
+          const uint64_t e0 = uint64_t(t.vec_off) * ve, e1 = e0 + t.n_elems;
+          CHECK(e1 <= row_elems(t.row));
+          covered[cls] += t.n_elems;
+          // ragged only at the very end of a tensor row (the fused row is whole granules)
+          if (t.n_elems % ve) CHECK(t.row != fused_row && e1 == elems[t.row]);
+          // position inside the unit -> segment -> first worker
+          uint64_t unit_pos = ~0ull;
+          if (un.kind == CARAMEL_KIND_CHUNK) {
+            const caramel_entry& e = p.entries[un.first_entry];
+            CHECK(t.row == e.tensor && e0 >= e.tensor_off && e1 <= e.tensor_off + e.elems);
+            unit_pos = e0 - e.tensor_off;
+          } else if (t.row == fused_row) {
+            CHECK(table == 0 && e0 >= un.fused_off && e1 <= un.fused_off + un.elems);
+            unit_pos = e0 - un.fused_off;
+          } else {
+            CHECK(table == 1);
+            bool found = false;
+            for (uint32_t k = 0; k < un.n_entries; ++k) {
+              const caramel_entry& e = p.entries[un.first_entry + k];
+              if (e.tensor == t.row) {
+                CHECK(e0 >= e.tensor_off && e1 <= e.tensor_off + e.elems);
+                unit_pos = e.unit_off + (e0 - e.tensor_off);
+                found = true;
+              }
             }
+            CHECK(found);
           }
-          CHECK(found);
+          uint32_t c = 0;
+          while (c + 1 < W && seg[c + 1] <= unit_pos) ++c;
+          CHECK(unit_pos >= seg[c] && unit_pos + t.n_elems <= seg[c + 1]);
+          CHECK(t.first == (cfg.pattern == CARAMEL_PATTERN_RING ? (c + 1) % W : 0));
+          // the class follows the length of the run (a ring run's first worker identifies its
+          // segment; the other patterns have first == 0 everywhere, so neighbours may merge:
+          // there only the lower bound of a long run can be checked)
+          const uint64_t rl = run_len(i) * es;
+          if (cls == kLong) CHECK(rl >= long_run_bytes);
+          else if (cfg.pattern == CARAMEL_PATTERN_RING && W > 1) CHECK(rl < long_run_bytes);
+          if ((addr_seed & 1) && (shape.align_tiles & (cls == kLong ? 2u : 1u))) {
+            // same phase in every replica: a tile that does not begin its run begins an aligned block
+            const bool continues = i > r.begin && prev_row == t.row && prev_end == e0 && prev_seg == c;
+            if (continues) CHECK((addr[size_t(t.row) * W] + e0 * es) % (cap * 16) == 0);
+          }
+          prev_row = t.row;
+          prev_end = e1;
+          prev_seg = c;
+          std::vector<uint8_t>& s = seen[t.row];
+          if (s.empty()) s.assign(row_elems(t.row), 0);
+          for (uint64_t e = e0; e < e1; ++e) {
+            CHECK(s[e] == 0);
+            s[e] = 1;
+          }
         }
-        uint32_t c = 0;
-        while (c + 1 < W && seg[c + 1] <= unit_pos) ++c;
-        CHECK(unit_pos >= seg[c] && unit_pos + t.n_elems <= seg[c + 1]);
-        CHECK(t.first == (cfg.pattern == CARAMEL_PATTERN_RING ? (c + 1) % W : 0));
-        if ((addr_seed & 1) && (shape.align_tiles & (is_large_unit(p, u, shape) ? 2u : 1u))) {
-          // same phase in every replica: a tile that does not begin its run begins an aligned block
-          const uint64_t cap_b = uint64_t(!is_large_unit(p, u, shape) ? small_vecs : (tt.long_launches[un.stream] ? tile_vecs : shape.medium_vecs)) * 16;
-          const bool continues = i > r.begin && prev_row == t.row && prev_end == e0 && prev_seg == c;
-          if (continues) CHECK((addr[size_t(t.row) * W] + e0 * es) % cap_b == 0);
-        }
-        prev_row = t.row;
-        prev_end = e1;
-        prev_seg = c;
-        std::vector<uint8_t>& s = seen[t.row];
-        if (s.empty()) s.assign(row_elems(t.row), 0);
-        for (uint64_t e = e0; e < e1; ++e) {
-          CHECK(s[e] == 0);
-          s[e] = 1;
-        }
+        CHECK(covered[cls] == per_unit[u].elems[cls]);
       }
+      // a unit's tiles cover its elements (the padding of a batch unit only in the fused buffer)
+      uint64_t want = un.elems;
+      if (un.kind == CARAMEL_KIND_BATCH && table == 1) {
+        want = 0;
+        for (uint32_t k = 0; k < un.n_entries; ++k) want += p.entries[un.first_entry + k].elems;
+      }
+      CHECK(covered[0] + covered[1] == want);
     }
     CHECK(total_tiles == tiles.size());
     // tensors: every element exactly once, except members of batch units in the staged table
@@ -146,16 +176,15 @@ static void check_case(const caramel_config& cfg, const std::vector<uint64_t>& e
       const std::vector<uint8_t>& s = seen[fused_row];
       CHECK(s.size() == p.fused_elems && std::all_of(s.begin(), s.end(), [](uint8_t b) { return b == 1; }));
     }
-    // the unit ranges follow one another in the documented order: large units of stream 0,
-    // of stream 1, small units of stream 0, of stream 1
+    // the unit ranges follow one another in the documented order: long tiles of the units of
+    // stream 0, of stream 1, then the small tiles likewise
     uint32_t at = 0;
     for (int cls = 0; cls < 2; ++cls)
       for (uint32_t s = 0; s < cfg.num_streams; ++s)
-        for (uint32_t u : tt.order[cls][s]) {
+        for (uint32_t u : tt.order[s]) {
           CHECK(p.units[u].stream == s);
-          CHECK(is_large_unit(p, u, shape) == (cls == kLarge));
-          CHECK(per_unit[u].begin == at);
-          at += per_unit[u].count;
+          CHECK(per_unit[u].tiles[cls].begin == at);
+          at += per_unit[u].tiles[cls].count;
         }
     CHECK(at == tiles.size());
   }
@@ -231,11 +260,11 @@ int main() {
     cfg.split_bytes = cfg.split_mode ? pick({1, 2, 4, 16, 64}) * std::max<uint64_t>(cfg.align_bytes, 64) : 0;
     cfg.num_streams = uint32_t(1 + rng() % 2);
     cfg.pattern = uint32_t(rng() % 3);
-    if (cfg.pattern == CARAMEL_PATTERN_HALVING_DOUBLING) cfg.world = uint32_t(pick({1, 2, 4, 8, 16}));
+    if (cfg.pattern == CARAMEL_PATTERN_HALVING_DOUBLING) cfg.world = uint32_t(pick({1, 2, 4, 8, 16, 32, 64}));
     std::vector<uint64_t> elems(1 + rng() % 14);
     for (uint64_t& e : elems) e = pick({1, 2, 3, 5, 8, 17, 64, 100, 255, 256, 257, 1000, 4096, 5000, 70000});
     check_case(cfg, elems, uint32_t(pick({64, 256, 1024, 4096})), uint32_t(pick({64, 256, 1024})),
-               pick({0, 1024, 65536, 1u << 22}), uint32_t(pick({64, 512})), it % 3 == 0 ? 0 : rng());
+               pick({0, 256, 1024, 16384, 65536, 1u << 22}), uint32_t(pick({64, 512})), it % 3 == 0 ? 0 : rng());
   }
   // rejected configurations must not crash
   HostPlan p;

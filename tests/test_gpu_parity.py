@@ -84,11 +84,12 @@ def test_allreduce_all_modes(W, dtype, launch, batch, streams):
     {cm.OPT_MAX_GRID: 7}, {cm.OPT_NONTEMPORAL: 0}, {cm.OPT_UNROLL: 2, cm.OPT_MAX_GRID: 300},
     {cm.OPT_LAUNCH_MIN_BYTES: 1 << 16}, {cm.OPT_LAUNCH_MIN_BYTES: 1 << 30, cm.OPT_BATCH_PATH: cm.BATCH_STAGED},
     {cm.OPT_LAUNCH_MIN_BYTES: 200000, cm.OPT_BATCH_PATH: cm.BATCH_STAGED},
-    {cm.OPT_STREAM_MAJOR: 4, cm.OPT_LARGE_UNIT_BYTES: 0, cm.OPT_LONG_LAUNCH_BYTES: 0, cm.OPT_TILE_VECS: 4096}, {cm.OPT_STREAM_MAJOR: 2, cm.OPT_LARGE_UNIT_BYTES: 0, cm.OPT_LONG_LAUNCH_BYTES: 0, cm.OPT_TILE_VECS: 512, cm.OPT_BLOCK: 256},
-    {cm.OPT_STREAM_MAJOR: 4, cm.OPT_LARGE_UNIT_BYTES: 65536, cm.OPT_LONG_LAUNCH_BYTES: 1, cm.OPT_TILE_VECS: 1024, cm.OPT_BLOCK: 256, cm.OPT_BATCH_PATH: cm.BATCH_STAGED},
-    {cm.OPT_LARGE_UNIT_BYTES: 0, cm.OPT_LONG_LAUNCH_BYTES: 0}, {cm.OPT_LARGE_UNIT_BYTES: 0, cm.OPT_LONG_LAUNCH_BYTES: 100000, cm.OPT_MEDIUM_TILE_VECS: 512},
-    {cm.OPT_LARGE_UNIT_BYTES: 0}, {cm.OPT_LARGE_UNIT_BYTES: 1 << 40}, {cm.OPT_LARGE_UNIT_BYTES: 100000, cm.OPT_SMALL_TILE_VECS: 64},
-    {cm.OPT_LARGE_UNIT_BYTES: 65536, cm.OPT_SMALL_BLOCK: 512, cm.OPT_SMALL_TILE_VECS: 1024, cm.OPT_BATCH_PATH: cm.BATCH_STAGED},
+    {cm.OPT_STREAM_MAJOR: 4, cm.OPT_LONG_RUN_BYTES: 0, cm.OPT_TILE_VECS: 4096},
+    {cm.OPT_STREAM_MAJOR: 2, cm.OPT_LONG_RUN_BYTES: 0, cm.OPT_TILE_VECS: 512, cm.OPT_BLOCK: 256},
+    {cm.OPT_STREAM_MAJOR: 4, cm.OPT_LONG_RUN_BYTES: 4096, cm.OPT_TILE_VECS: 1024, cm.OPT_BLOCK: 256, cm.OPT_BATCH_PATH: cm.BATCH_STAGED},
+    {cm.OPT_LONG_RUN_BYTES: 0}, {cm.OPT_LONG_RUN_BYTES: 0, cm.OPT_STREAM_MAJOR: 0}, {cm.OPT_LONG_RUN_BYTES: 1 << 40},
+    {cm.OPT_LONG_RUN_BYTES: 100000, cm.OPT_SMALL_TILE_VECS: 64}, {cm.OPT_LONG_RUN_BYTES: 2048, cm.OPT_LONG_LAUNCH_MIN_BYTES: 0},
+    {cm.OPT_LONG_RUN_BYTES: 65536, cm.OPT_SMALL_BLOCK: 512, cm.OPT_SMALL_TILE_VECS: 1024, cm.OPT_BATCH_PATH: cm.BATCH_STAGED},
     {cm.OPT_BLOCK: 256}, {cm.OPT_BLOCK: 1024, cm.OPT_TILE_VECS: 2048}, {cm.OPT_BLOCK: 1024, cm.OPT_TILE_VECS: 128},
 ])
 @pytest.mark.parametrize("dtype", [oracle.F32, oracle.BF16])
@@ -126,19 +127,40 @@ def test_alignment_and_split_modes(align, mode, S):
 @pytest.mark.parametrize("phase", [0, 256, 1280, 4096 - 256, 65536 - 512])
 @pytest.mark.parametrize("align_tiles", [0, 1, 2, 3])
 def test_tiles_cut_on_aligned_blocks_give_the_same_bits(phase, align_tiles):
-    """Every replica at the same position inside an aligned block: small tiles (bit 0) and medium
+    """Every replica at the same position inside an aligned block: small tiles (bit 0) and long
     tiles (bit 1) are then cut on multiples of their size in memory, with a short first tile."""
     print(f"case: aligned tiles phase={phase} align_tiles={align_tiles}", flush=True)
     cfg = small_cfg(8, oracle.F32)
     elems = list(SMALL_ELEMS)
     grads = make_inputs(cfg, elems, seed=11)
     ref = oracle_result(cfg, elems, grads)
-    for extra in ({}, {cm.OPT_LARGE_UNIT_BYTES: 65536, cm.OPT_MEDIUM_TILE_VECS: 256, cm.OPT_BATCH_PATH: cm.BATCH_STAGED}):
+    for extra in ({}, {cm.OPT_LONG_RUN_BYTES: 8192, cm.OPT_TILE_VECS: 256, cm.OPT_BLOCK: 256, cm.OPT_BATCH_PATH: cm.BATCH_STAGED}):
         plan = lib_plan(cfg, elems, {cm.OPT_ALIGN_TILES: align_tiles, cm.OPT_SMALL_TILE_VECS: 64, **extra})
         dev = Replicas(plan, elems, slot_align=256, large_align=256, arena_phase=phase)
         dev.upload(grads)
         plan.allreduce()
         assert_same_bits(dev.download(), ref, f"phase {phase}, align_tiles {align_tiles}, {extra}")
+        plan.close()
+
+
+@pytest.mark.parametrize("phase", [0, 256, 1280, 20480, 39936, 65536 - 512])
+@pytest.mark.parametrize("dtype", [oracle.F32, oracle.BF16])
+def test_long_tiles_cut_on_aligned_blocks_give_the_same_bits(phase, dtype):
+    """Long launches over tensors that do not start on a tile boundary in memory: the first and
+    last tile of every run are short (1 to 4 rows of lanes, the last row ragged) and are walked
+    by the stream-major kernel like the whole ones."""
+    print(f"case: long tiles phase={phase} dtype={dtype}", flush=True)
+    cfg = oracle.Config(8, dtype, 8192, oracle.SPLIT_FIXED, 8, 1 << 20, 16, 2)
+    elems = [600000, 33, 262144 + 4, 5000, 1 << 20]
+    grads = make_inputs(cfg, elems, seed=12)
+    ref = oracle_result(cfg, elems, grads)
+    for tile, block, sm in ((4096, 1024, 4), (1024, 256, 4), (2048, 1024, 2)):
+        plan = lib_plan(cfg, elems, {cm.OPT_LONG_RUN_BYTES: 4096,
+                                     cm.OPT_TILE_VECS: tile, cm.OPT_BLOCK: block, cm.OPT_STREAM_MAJOR: sm})
+        dev = Replicas(plan, elems, slot_align=256, large_align=256, arena_phase=phase)
+        dev.upload(grads)
+        plan.allreduce()
+        assert_same_bits(dev.download(), ref, f"phase {phase}, tile {tile}, block {block}")
         plan.close()
 
 
@@ -244,16 +266,31 @@ def test_profile_counters():
         for _ in range(3):
             plan.allreduce()
         st = plan.profile_read()
-        # one reduce launch per stream and call; pack/unpack only on streams that own batch units
-        assert st[cm.K_REDUCE]["launches"] == 6
+        # every run of this small case is short: one launch over small tiles per stream and call,
+        # none over long tiles; pack/unpack only on streams that own batch units
+        red = st[cm.K_REDUCE_SMALL]
+        assert red["launches"] == 6 and st[cm.K_REDUCE]["launches"] == 0
+        units = plan.units()
+        assert red["elements"] == 3 * sum(u.elems for u in units)        # batch units with their padding
         assert st[cm.K_PACK]["launches"] == st[cm.K_UNPACK]["launches"] and st[cm.K_PACK]["launches"] in (3, 6)
         seq = st[cm.K_SEQUENCE]
         assert seq["launches"] == 6 and seq["calls"] == 3 and seq["total_ms"] > 0 and seq["span_ms"] > 0
         if level == 2:
-            assert st[cm.K_REDUCE]["calls"] == 3 and st[cm.K_REDUCE]["total_ms"] > 0
-            assert st[cm.K_REDUCE]["total_ms"] <= seq["total_ms"]
+            assert red["calls"] == 3 and red["total_ms"] > 0
+            assert red["total_ms"] <= seq["total_ms"]
         else:
-            assert st[cm.K_REDUCE]["total_ms"] == 0
+            assert red["total_ms"] == 0
+    # with a lower limit the long runs go out in launches of their own
+    plan.close()
+    plan = lib_plan(cfg, elems, {cm.OPT_LONG_RUN_BYTES: 4096})
+    dev = Replicas(plan, elems)
+    dev.upload(make_inputs(cfg, elems, seed=3))
+    plan.profile(1)
+    plan.allreduce()
+    st = plan.profile_read()
+    assert st[cm.K_REDUCE]["launches"] == 1 and st[cm.K_REDUCE_SMALL]["launches"] == 1      # AUTO: one per class
+    assert st[cm.K_REDUCE]["elements"] + st[cm.K_REDUCE_SMALL]["elements"] == sum(elems)   # in place: no padding
+    assert st[cm.K_REDUCE]["elements"] > 0
     plan.profile(0)
     plan.close()
 
@@ -261,7 +298,8 @@ def test_profile_counters():
 # ------------------------------------------------------------------ other patterns, timed plans
 @pytest.mark.parametrize("pattern", [oracle.PATTERN_HALVING_DOUBLING, oracle.PATTERN_SHUFFLE])
 @pytest.mark.parametrize("W,dtype", [(1, oracle.F32), (2, oracle.F32), (4, oracle.F32), (8, oracle.F32), (16, oracle.F32),
-                                     (4, oracle.BF16), (8, oracle.BF16), (16, oracle.BF16)])
+                                     (4, oracle.BF16), (8, oracle.BF16), (16, oracle.BF16),
+                                     (32, oracle.F32), (64, oracle.F32), (32, oracle.BF16), (64, oracle.BF16)])
 def test_other_patterns_match_the_oracle(pattern, W, dtype):
     print(f"case: pattern={pattern} W={W} dtype={dtype}", flush=True)
     cfg = oracle.Config(W, dtype, 8192, oracle.SPLIT_FIXED, 8, 65536, 16, 2, pattern)
@@ -286,7 +324,7 @@ def test_world_sizes_of_the_generic_kernel_including_the_maximum(W, dtype):
     elems = list(SMALL_ELEMS)
     grads = make_inputs(cfg, elems, seed=60 + W)
     ref = oracle_result(cfg, elems, grads)
-    for opts in ({}, {cm.OPT_LARGE_UNIT_BYTES: 0, cm.OPT_LONG_LAUNCH_BYTES: 0, cm.OPT_TILE_VECS: 4096}):
+    for opts in ({}, {cm.OPT_LONG_RUN_BYTES: 0, cm.OPT_TILE_VECS: 4096}, {cm.OPT_LONG_RUN_BYTES: 1 << 40}):
         plan = lib_plan(cfg, elems, opts)
         dev = Replicas(plan, elems)
         dev.upload(grads)

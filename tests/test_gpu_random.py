@@ -23,7 +23,7 @@ def draw(rng: random.Random):
     pattern = rng.choice([oracle.PATTERN_RING, oracle.PATTERN_RING, oracle.PATTERN_HALVING_DOUBLING,
                           oracle.PATTERN_SHUFFLE])
     if pattern == oracle.PATTERN_HALVING_DOUBLING:
-        W = rng.choice([1, 2, 4, 8, 16])
+        W = rng.choice([1, 2, 4, 8, 16, 32, 64])
     else:
         W = rng.choice([1, 2, 3, 4, 5, 7, 8, 8, 9, 12, 16, 16, 20, 33])
     dtype = rng.choice([oracle.F32, oracle.BF16])
@@ -38,11 +38,10 @@ def draw(rng: random.Random):
             cm.OPT_PIPELINE_MIN_BYTES: rng.choice([0, 1 << 40]),
             cm.OPT_SMALL_TILE_VECS: rng.choice([64, 256, 1024]),
             cm.OPT_SMALL_BLOCK: rng.choice([256, 512, 1024]),
-            cm.OPT_MEDIUM_TILE_VECS: rng.choice([128, 1024]),
             cm.OPT_TILE_VECS: rng.choice([512, 4096]),
             cm.OPT_BLOCK: rng.choice([256, 1024]),
-            cm.OPT_LARGE_UNIT_BYTES: rng.choice([0, 65536, 4 << 20]),
-            cm.OPT_LONG_LAUNCH_BYTES: rng.choice([0, 200000, 64 << 20]),
+            cm.OPT_LONG_RUN_BYTES: rng.choice([0, 1024, 32768, 32768, 1 << 40]),
+            cm.OPT_LONG_LAUNCH_MIN_BYTES: rng.choice([0, 200000, 64 << 20]),
             cm.OPT_STREAM_MAJOR: rng.choice([0, 2, 4]),
             cm.OPT_ALIGN_TILES: rng.choice([0, 1, 2, 3]),
             cm.OPT_LAUNCH_MIN_BYTES: rng.choice([0, 65536, 4 << 20]),

@@ -84,6 +84,50 @@ def test_serialized_image_is_canonical():
     assert c.serialize() != img
 
 
+def decode_image(img: bytes):
+    """Reader for the layout documented at caramel_plan_serialize."""
+    assert img[:8] == b"CARAMEL1"
+    at = 8
+    def take(fmt):
+        nonlocal at
+        vals = struct.unpack_from("<" + fmt, img, at)
+        at += struct.calcsize("<" + fmt)
+        return vals
+    cfg = take("IIQIIQIII")
+    n_tensors, n_units, n_entries, fused = take("IIIQ")
+    elems = list(take(f"{n_tensors}Q"))
+    units = [take("IIIIQQ") for _ in range(n_units)]
+    entries = [take("IIQQQ") for _ in range(n_entries)]
+    segs = [list(take(f"{cfg[0] + 1}Q")) for _ in range(n_units)]
+    assert at == len(img) == 72 + 8 * n_tensors + 32 * n_units + 32 * n_entries + 8 * n_units * (cfg[0] + 1)
+    return cfg, elems, fused, units, entries, segs
+
+
+@pytest.mark.parametrize("name", ["mlp", "resnet50", "vgg16", "inception_v3", "transformer"])
+def test_serialized_image_decodes_to_the_oracle_plan(name):
+    """Every field of the image, read back by the documented layout, against the oracle's plan."""
+    wl = workload(name)
+    elems = wl.elems()
+    cfg = oracle.Config(wl.world, wl.dtype, wl.batch_threshold_bytes, wl.split_mode, wl.max_depth,
+                        wl.split_bytes, wl.align_bytes, wl.num_streams)
+    op = oracle.build_plan(cfg, elems)
+    p = cm.Plan(wl.world, elems, dtype=wl.dtype, batch_threshold_bytes=wl.batch_threshold_bytes,
+                split_mode=wl.split_mode, split_bytes=wl.split_bytes, max_depth=wl.max_depth,
+                align_bytes=wl.align_bytes, num_streams=wl.num_streams)
+    c, t_elems, fused, units, entries, segs = decode_image(p.serialize())
+    p.close()
+    assert c == (cfg.world, cfg.dtype, cfg.batch_threshold_bytes, cfg.split_mode, cfg.max_depth, cfg.split_bytes,
+                 cfg.align_bytes, cfg.num_streams, cfg.pattern)
+    assert t_elems == list(elems) and fused == op.fused_elems
+    assert len(units) == len(op.units) and len(entries) == len(op.entries)
+    for got, u in zip(units, op.units):
+        assert got == (u.kind, u.stream, u.first_entry, u.n_entries, u.elems, u.fused_off)
+    for got, e in zip(entries, op.entries):
+        assert got == (e.tensor, e.unit, e.tensor_off, e.unit_off, e.elems)
+    for got, u in zip(segs, op.units):
+        assert got == list(u.seg_start)
+
+
 @pytest.mark.parametrize("kw", [
     dict(world=0), dict(world=65), dict(dtype=5), dict(align_bytes=8), dict(align_bytes=48),
     dict(num_streams=0), dict(num_streams=3), dict(split_mode=3),
@@ -194,6 +238,11 @@ def test_net_model_fit():
     assert a == pytest.approx(float(fa), rel=1e-9) and b == pytest.approx(float(fb), rel=1e-12)
     with pytest.raises(cm.CaramelError):
         cm.net_model_fit(64, 1.0, 64, 2.0)
+    # two noisy probes: the larger transfer measured faster, or a line that starts below zero
+    for t1, t2 in ((20.0, 18.0), (20.0, 20.0), (1.0, 1.0e9)):
+        with pytest.raises(cm.CaramelError) as ei:
+            cm.net_model_fit(64, t1, 4 << 20, t2)
+        assert ei.value.status == binding.EINVAL and "probes" in str(ei.value)
 
 
 def test_header_is_plain_c_and_the_library_links_from_c(tmp_path):
