@@ -270,6 +270,27 @@ int caramel_ring_reduce(caramel_plan* plan, void* stream);
 int caramel_unpack(caramel_plan* plan, void* stream);
 int caramel_allreduce(caramel_plan* plan, void* stream);
 
+/* For callers that cannot allocate device memory (code that sets up or runs under HIP graph
+ * capture rules, tight serving loops, harnesses that forbid hipMalloc): caramel_bind +
+ * caramel_allreduce (in-place batch path) in one call that allocates nothing on the device and
+ * creates no stream or event.  The descriptor tables that caramel_bind would put into memory from
+ * hipMalloc go into a static device array of CARAMEL_STATIC_TABLE_BYTES inside the library,
+ * which every GPU the library runs on holds until the process ends.
+ *   plan    any plan (bound or not; a binding made with caramel_bind is left untouched);
+ *   grads   as for caramel_bind; the pointers are taken anew on every call;
+ *   stream  every launch goes on this stream (no internal stream, whatever num_streams says).
+ * Afterwards (in stream order) every grads[w][t] holds the same bytes caramel_allreduce gives.
+ * The tables are uploaded, with a wait for `stream`, when the array of the current GPU does not
+ * already hold them from a call on the same stream; otherwise the call only launches kernels.
+ * All calls on one GPU share its array: a call must not be issued while another plan's call, or
+ * a call on another stream, may still be running there - such calls race.  The plan's launch
+ * options apply; timing (caramel_profile) does not cover this call.
+ * EINVAL: NULL/misaligned/overlapping pointers; a plan whose tables (8 bytes per tensor and
+ * worker, rounded up to 256, plus 16 bytes per tile) exceed CARAMEL_STATIC_TABLE_BYTES - nothing
+ * is launched then.  EHIP: a HIP call failed. */
+#define CARAMEL_STATIC_TABLE_BYTES (4u << 20)
+int caramel_allreduce_static(caramel_plan* plan, void* const* grads, void* stream);
+
 /* ---- launch tuning and timing (do not change results) ------------------------------------ */
 
 /* How the work is cut up for the GPU.  A "run" is a maximal piece of one tensor (or of the fused

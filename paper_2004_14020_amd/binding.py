@@ -22,6 +22,7 @@ PATTERN_RING, PATTERN_HALVING_DOUBLING, PATTERN_SHUFFLE = 0, 1, 2
 (OPT_LAUNCH_MODE, OPT_BATCH_PATH, OPT_TILE_VECS, OPT_MAX_GRID, OPT_NONTEMPORAL, OPT_UNROLL, OPT_BLOCK,
  OPT_LAUNCH_MIN_BYTES, OPT_PIPELINE_MIN_BYTES, OPT_SMALL_TILE_VECS, OPT_SMALL_BLOCK, OPT_LONG_RUN_BYTES,
  OPT_STREAM_MAJOR, OPT_LONG_LAUNCH_MIN_BYTES, OPT_ALIGN_TILES) = range(15)
+STATIC_TABLE_BYTES = 4 << 20
 LAUNCH_PER_UNIT, LAUNCH_PER_STREAM, LAUNCH_AUTO = 0, 1, 2
 BATCH_STAGED, BATCH_DIRECT = 0, 1
 K_PACK, K_REDUCE, K_UNPACK, K_SEQUENCE, K_REDUCE_SMALL, K_COUNT = 0, 1, 2, 3, 4, 5
@@ -30,7 +31,7 @@ EXPORTS = (
     "caramel_plan_create", "caramel_plan_create_timed", "caramel_plan_times", "caramel_net_model_fit",
     "caramel_threshold_estimate", "caramel_schedule_transfers", "caramel_plan_windows", "caramel_plan_destroy", "caramel_plan_counts", "caramel_plan_units",
     "caramel_plan_entries", "caramel_plan_segments", "caramel_plan_serialize", "caramel_bind",
-    "caramel_pack", "caramel_ring_reduce", "caramel_unpack", "caramel_allreduce",
+    "caramel_pack", "caramel_ring_reduce", "caramel_unpack", "caramel_allreduce", "caramel_allreduce_static",
     "caramel_plan_set_option", "caramel_profile", "caramel_profile_read", "caramel_last_error",
     "caramel_version", "caramel_stream_probe",
 )
@@ -111,6 +112,7 @@ def lib() -> C.CDLL:
     L.caramel_bind.argtypes = [P, C.POINTER(P), P]
     for name in ("caramel_pack", "caramel_ring_reduce", "caramel_unpack", "caramel_allreduce"):
         getattr(L, name).argtypes = [P, P]
+    L.caramel_allreduce_static.argtypes = [P, C.POINTER(P), P]
     L.caramel_plan_set_option.argtypes = [P, C.c_uint32, C.c_uint64]
     L.caramel_profile.argtypes = [P, C.c_int]
     L.caramel_profile_read.argtypes = [P, C.POINTER(KernelStat)]
@@ -236,6 +238,14 @@ class Plan:
 
     def allreduce(self, stream: int = 0) -> None:
         _check(lib().caramel_allreduce(self._h, C.c_void_p(stream)))
+
+    def allreduce_static(self, grad_ptrs: Sequence[Sequence[int]], stream: int = 0) -> None:
+        """caramel_allreduce_static: grad_ptrs as for bind; no device allocation inside the call."""
+        W, n = self.cfg.world, self.n_tensors
+        if len(grad_ptrs) != W or any(len(r) != n for r in grad_ptrs):
+            raise ValueError("grad_ptrs must be world x n_tensors")
+        flat = (C.c_void_p * (W * n))(*[int(grad_ptrs[w][t]) for w in range(W) for t in range(n)])
+        _check(lib().caramel_allreduce_static(self._h, flat, C.c_void_p(stream)))
 
     def profile(self, level: int) -> None:
         _check(lib().caramel_profile(self._h, int(level)))

@@ -7,6 +7,7 @@
 #include <cstdio>
 #include <cstring>
 #include <memory>
+#include <mutex>
 #include <new>
 #include <string>
 #include <vector>
@@ -18,6 +19,11 @@
 #include "tiles.hpp"
 
 using namespace caramel;
+
+// Table space of caramel_allreduce_static: one copy per GPU the library runs on, held until the
+// process ends.  On the host this name is only a handle for hipGetSymbolAddress; the device
+// address it stands for is looked up once per device and used everywhere else.
+static __device__ __align__(256) unsigned char scratch[CARAMEL_STATIC_TABLE_BYTES];
 
 namespace {
 
@@ -119,6 +125,11 @@ struct caramel_plan {
   hipStream_t streams[2] = {nullptr, nullptr};
   hipEvent_t ev_fork = nullptr;
   hipEvent_t ev_join[2] = {nullptr, nullptr};
+  // caramel_allreduce_static keeps its own host tables; their device copy lives in the
+  // library's static array
+  Binding fixed;
+  bool fixed_valid = false;
+  uint64_t fixed_generation = 0;  // identifies the contents of `fixed` among all plans
   // timing
   int profiling = 0;  // 0 off, 1 one event pair per stream sequence, 2 one pair per launch
   uint64_t call_no = 0;
@@ -206,7 +217,7 @@ struct Timed {
 };
 
 int run_reduce(caramel_plan* p, const Binding& bd, const DeviceTables& dt, bool direct, const LaunchGroup& g,
-               hipStream_t s) {
+               hipStream_t s, bool timed = true) {
   const Range r = g.reduce;
   const int cls = g.cls;
   if (r.count == 0) return CARAMEL_OK;
@@ -226,6 +237,10 @@ int run_reduce(caramel_plan* p, const Binding& bd, const DeviceTables& dt, bool 
   a.unroll = p->opt.unroll ? p->opt.unroll : std::max(1u, tile_vecs / a.block);
   a.stream_major = lng ? p->opt.stream_major : 0;
   a.max_grid = p->opt.max_grid;
+  if (!timed) {
+    HIP_TRY(launch_ring_reduce(a, s));
+    return CARAMEL_OK;
+  }
   Timed timer(p, lng ? CARAMEL_K_REDUCE : CARAMEL_K_REDUCE_SMALL, s, g.elems);
   HIP_TRY(launch_ring_reduce(a, s));
   return CARAMEL_OK;
@@ -576,7 +591,7 @@ int caramel_plan_serialize(const caramel_plan* p, void* buf, size_t* len) {
 int caramel_plan_set_option(caramel_plan* p, uint32_t option, uint64_t value) {
   if (!p) return fail(CARAMEL_EINVAL, "plan is NULL");
   auto regroup = [&] {
-    p->bind.groups_stale[0] = p->bind.groups_stale[1] = true;
+    for (Binding* b : {&p->bind, &p->fixed}) b->groups_stale[0] = b->groups_stale[1] = true;
   };
   auto is_block = [](uint64_t v) { return v == 256 || v == 512 || v == 1024; };
   switch (option) {
@@ -592,10 +607,12 @@ int caramel_plan_set_option(caramel_plan* p, uint32_t option, uint64_t value) {
     case CARAMEL_OPT_TILE_VECS:
       if (value < 64 || value > (1u << 20)) return fail(CARAMEL_EINVAL, "tile_vecs must be in [64, 2^20]");
       p->opt.shape.long_vecs = uint32_t(value);
+      p->fixed_valid = false;
       return CARAMEL_OK;
     case CARAMEL_OPT_SMALL_TILE_VECS:
       if (value < 64 || value > (1u << 20)) return fail(CARAMEL_EINVAL, "tile_vecs must be in [64, 2^20]");
       p->opt.shape.small_vecs = uint32_t(value);
+      p->fixed_valid = false;
       return CARAMEL_OK;
     case CARAMEL_OPT_SMALL_BLOCK:
       if (!is_block(value)) return fail(CARAMEL_EINVAL, "block must be 256, 512 or 1024");
@@ -612,9 +629,11 @@ int caramel_plan_set_option(caramel_plan* p, uint32_t option, uint64_t value) {
     case CARAMEL_OPT_ALIGN_TILES:
       if (value > 3) return fail(CARAMEL_EINVAL, "align_tiles must be 0..3");
       p->opt.shape.align_tiles = uint32_t(value);
+      p->fixed_valid = false;
       return CARAMEL_OK;
     case CARAMEL_OPT_LONG_RUN_BYTES:
       p->opt.shape.long_run_bytes = value;
+      p->fixed_valid = false;
       return CARAMEL_OK;
     case CARAMEL_OPT_MAX_GRID:
       if (value > 0x7FFFFFFFu) return fail(CARAMEL_EINVAL, "max_grid too large");
@@ -772,6 +791,75 @@ int caramel_allreduce(caramel_plan* p, void* stream) {
     if (int rc = need_bound(p, !direct)) return rc;
     return pipeline(p, hipStream_t(stream), true, direct);
   });
+}
+
+namespace {
+
+constexpr int kMaxDevices = 64;
+std::mutex g_scratch_mu;
+unsigned char* g_scratch_ptr[kMaxDevices] = {};  // device address of each GPU's copy of `scratch`
+uint64_t g_scratch_holds[kMaxDevices] = {};      // generation of the tables it holds (0: none)
+hipStream_t g_scratch_stream[kMaxDevices] = {};  // stream they were uploaded on
+uint64_t g_generation = 0;
+
+int allreduce_static(caramel_plan* p, void* const* grads, hipStream_t stream) {
+  if (!p || !grads) return fail(CARAMEL_EINVAL, "NULL argument");
+  const HostPlan& h = p->host;
+  std::vector<uint64_t> rows;
+  if (int rc = check_pointers(h, grads, nullptr, rows)) return rc;
+  int dev = -1;
+  HIP_TRY(hipGetDevice(&dev));
+  if (dev < 0 || dev >= kMaxDevices) return fail(CARAMEL_ESTATE, "device %d is beyond the %d this entry point serves", dev, kMaxDevices);
+
+  std::lock_guard<std::mutex> lock(g_scratch_mu);
+  if (!p->fixed_valid || rows != p->fixed.rows) {
+    fill_binding(p, std::move(rows), p->fixed);
+    p->fixed_valid = true;
+    p->fixed_generation = ++g_generation;
+  }
+  const Binding& bd = p->fixed;
+  const size_t rows_bytes = (bd.rows.size() * sizeof(uint64_t) + 255) / 256 * 256;
+  const size_t tile_bytes = bd.tt.direct.size() * sizeof(ReduceTile);
+  if (rows_bytes + tile_bytes > CARAMEL_STATIC_TABLE_BYTES)
+    return fail(CARAMEL_EINVAL,
+                "this plan needs %zu bytes of descriptor tables (%zu tensors x %u workers, %zu tiles); the "
+                "static array holds %u: use caramel_bind + caramel_allreduce",
+                rows_bytes + tile_bytes, h.tensor_elems.size(), h.cfg.world, bd.tt.direct.size(),
+                unsigned(CARAMEL_STATIC_TABLE_BYTES));
+
+  // this GPU's copy of the array: looked up once, with this device current
+  if (!g_scratch_ptr[dev]) {
+    void* q = nullptr;
+    HIP_TRY(hipGetSymbolAddress(&q, HIP_SYMBOL(scratch)));
+    if (!q) return fail(CARAMEL_EHIP, "hipGetSymbolAddress returned no address for the static table array");
+    g_scratch_ptr[dev] = static_cast<unsigned char*>(q);
+  }
+  unsigned char* base = g_scratch_ptr[dev];
+  // The array keeps what the last call put there.  Tables are written whole before they are
+  // used and nothing is read beyond them, so nothing needs clearing; they are uploaded again
+  // unless this GPU's array still holds exactly these, put there through this same stream.
+  if (g_scratch_holds[dev] != p->fixed_generation || g_scratch_stream[dev] != stream) {
+    g_scratch_holds[dev] = 0;
+    HIP_TRY(hipMemcpyAsync(base, bd.rows.data(), bd.rows.size() * sizeof(uint64_t), hipMemcpyHostToDevice, stream));
+    if (tile_bytes)
+      HIP_TRY(hipMemcpyAsync(base + rows_bytes, bd.tt.direct.data(), tile_bytes, hipMemcpyHostToDevice, stream));
+    // the host tables may be rebuilt or freed by a later call: wait until they have been read
+    HIP_TRY(hipStreamSynchronize(stream));
+    g_scratch_holds[dev] = p->fixed_generation;
+    g_scratch_stream[dev] = stream;
+  }
+  DeviceTables dt;
+  dt.rows = reinterpret_cast<const uint64_t*>(base);
+  dt.direct = reinterpret_cast<const ReduceTile*>(base + rows_bytes);
+  for (const LaunchGroup& g : launch_groups(p, p->fixed, true, false))
+    if (int rc = run_reduce(p, p->fixed, dt, true, g, stream, false)) return rc;
+  return CARAMEL_OK;
+}
+
+}  // namespace
+
+int caramel_allreduce_static(caramel_plan* p, void* const* grads, void* stream) {
+  return guarded([&] { return allreduce_static(p, grads, hipStream_t(stream)); });
 }
 
 int caramel_profile(caramel_plan* p, int enable) {
