@@ -195,6 +195,10 @@ def main() -> int:
     plan.profile(0)
     prof_steps = args.profile_steps
 
+    # the same calls issued from inside the library: what a call costs the host, and what it
+    # costs on the stream, without the interpreter in between
+    host_us, stream_us = plan.allreduce_loop(max(args.steps, 100), stream)
+
     ms_per_step = (t1 - t0) * 1e3 / args.steps
     alg_bytes = wl.algorithmic_bytes()
     gbs = alg_bytes / (ms_per_step * 1e-3) / 1e9
@@ -210,7 +214,7 @@ def main() -> int:
     def kernel_line(st):
         if not st["launches"]:
             return None
-        out = {"launches_per_step": st["launches"] / prof_steps,
+        out = {"launches_per_step": st["launches"] / max(1, prof_steps),
                "bytes_per_launch": round(per_elem * st["elements"] / st["launches"])}
         if st["total_ms"] > 0:
             out["avg_launch_ms"] = round(st["total_ms"] / st["launches"], 6)
@@ -232,6 +236,8 @@ def main() -> int:
                 "step_frac": round(gbs / HBM_PEAK_GBS, 4),
                 "timed_region_event_ms_per_step": round(region_ms / args.steps, 5),
                 "per_launch_event_steps": prof_steps}
+    c_loop = {"host_us_per_call": round(host_us, 2), "stream_us_per_call": round(stream_us, 2),
+              "GB/s_on_stream": round(alg_bytes / stream_us / 1e3, 1)}
 
     cpu = None
     if not args.no_cpu_baseline:
@@ -290,6 +296,7 @@ def main() -> int:
                    "units": plan.counts()[0], "num_streams": streams,
                    "pattern": args.pattern, "launch_mode": args.launch_mode or "auto", "batch_path": args.batch_path or "direct"},
         "roofline": roofline,
+        "calls_issued_from_c": c_loop,
         "cpu_baseline": cpu,
     }
     print(json.dumps(out))

@@ -351,7 +351,12 @@ enum {
    * modulo the tile size, tiles are cut so that they start on multiples of the tile size in
    * memory (the first tile of a run is shortened); otherwise tiles start where their run starts.
    * Default 3.  Takes effect at the next caramel_bind.  Results do not depend on it. */
-  CARAMEL_OPT_ALIGN_TILES = 14
+  CARAMEL_OPT_ALIGN_TILES = 14,
+  /* One launch per tile class on one stream (PER_STREAM without the pipeline, which is what AUTO
+   * does): if the small tiles cover at most this many bytes per replica, they join the launch
+   * over the long tiles instead of getting a launch of their own.  Default 1 MiB; 0 keeps the
+   * two launches apart. */
+  CARAMEL_OPT_MERGE_SMALL_BYTES = 15
 };
 enum { CARAMEL_LAUNCH_PER_UNIT = 0, CARAMEL_LAUNCH_PER_STREAM = 1, CARAMEL_LAUNCH_AUTO = 2 };
 enum { CARAMEL_BATCH_STAGED = 0, CARAMEL_BATCH_DIRECT = 1 };
@@ -399,6 +404,14 @@ int caramel_profile(caramel_plan* plan, int level);
 int caramel_profile_read(caramel_plan* plan, caramel_kernel_stat* out);
 
 /* ---- measurement aid -------------------------------------------------------------------- */
+
+/* n_calls calls of caramel_allreduce issued back to back from inside the library, so that no
+ * caller-side cost (an interpreter, a foreign-function call) sits between them.  Reports the
+ * host time to issue one call (wall clock around the loop, no waiting for the GPU) and the
+ * time one call takes on the stream (a pair of HIP events around the loop, after the stream has
+ * drained).  Creates and destroys two events; otherwise like caramel_allreduce. */
+int caramel_allreduce_loop(caramel_plan* plan, void* stream, uint32_t n_calls, double* host_us_per_call,
+                           double* stream_us_per_call);
 
 /* Plain streaming kernels of exactly known traffic, with no descriptor tables: ceilings to set
  * the reduce kernels against, and kernels to check a profiler's memory counters with.

@@ -21,7 +21,7 @@ KIND_BATCH, KIND_CHUNK = 0, 1
 PATTERN_RING, PATTERN_HALVING_DOUBLING, PATTERN_SHUFFLE = 0, 1, 2
 (OPT_LAUNCH_MODE, OPT_BATCH_PATH, OPT_TILE_VECS, OPT_MAX_GRID, OPT_NONTEMPORAL, OPT_UNROLL, OPT_BLOCK,
  OPT_LAUNCH_MIN_BYTES, OPT_PIPELINE_MIN_BYTES, OPT_SMALL_TILE_VECS, OPT_SMALL_BLOCK, OPT_LONG_RUN_BYTES,
- OPT_STREAM_MAJOR, OPT_LONG_LAUNCH_MIN_BYTES, OPT_ALIGN_TILES) = range(15)
+ OPT_STREAM_MAJOR, OPT_LONG_LAUNCH_MIN_BYTES, OPT_ALIGN_TILES, OPT_MERGE_SMALL_BYTES) = range(16)
 STATIC_TABLE_BYTES = 4 << 20
 LAUNCH_PER_UNIT, LAUNCH_PER_STREAM, LAUNCH_AUTO = 0, 1, 2
 BATCH_STAGED, BATCH_DIRECT = 0, 1
@@ -33,7 +33,7 @@ EXPORTS = (
     "caramel_plan_entries", "caramel_plan_segments", "caramel_plan_serialize", "caramel_bind",
     "caramel_pack", "caramel_ring_reduce", "caramel_unpack", "caramel_allreduce", "caramel_allreduce_static",
     "caramel_plan_set_option", "caramel_profile", "caramel_profile_read", "caramel_last_error",
-    "caramel_version", "caramel_stream_probe",
+    "caramel_version", "caramel_stream_probe", "caramel_allreduce_loop",
 )
 
 
@@ -119,6 +119,7 @@ def lib() -> C.CDLL:
     L.caramel_last_error.restype = C.c_char_p
     L.caramel_last_error.argtypes = []
     L.caramel_version.argtypes = []
+    L.caramel_allreduce_loop.argtypes = [P, P, C.c_uint32, C.POINTER(C.c_double), C.POINTER(C.c_double)]
     L.caramel_stream_probe.argtypes = [C.c_uint32, C.POINTER(P), C.c_uint32, C.c_uint64, C.c_uint32, C.c_uint32, P]
     _lib = L
     return L
@@ -246,6 +247,12 @@ class Plan:
             raise ValueError("grad_ptrs must be world x n_tensors")
         flat = (C.c_void_p * (W * n))(*[int(grad_ptrs[w][t]) for w in range(W) for t in range(n)])
         _check(lib().caramel_allreduce_static(self._h, flat, C.c_void_p(stream)))
+
+    def allreduce_loop(self, n_calls: int, stream: int = 0):
+        """(host microseconds to issue one call, microseconds one call takes on the stream)."""
+        host, dev = C.c_double(), C.c_double()
+        _check(lib().caramel_allreduce_loop(self._h, C.c_void_p(stream), n_calls, C.byref(host), C.byref(dev)))
+        return host.value, dev.value
 
     def profile(self, level: int) -> None:
         _check(lib().caramel_profile(self._h, int(level)))

@@ -2,6 +2,7 @@
 #include <hip/hip_runtime.h>
 
 #include <algorithm>
+#include <chrono>
 #include <cmath>
 #include <cstdarg>
 #include <cstdio>
@@ -70,6 +71,7 @@ struct Options {
   uint64_t launch_min_bytes = 4u << 20;        // launches over small tiles: units share one up to this size
   uint64_t long_launch_min_bytes = 64u << 20;  // launches over long tiles likewise
   uint64_t pipeline_min_bytes = ~uint64_t(0);  // AUTO never pipelines unless told to
+  uint64_t merge_small_bytes = 1u << 20;       // one launch per stream: small tiles up to this total join the long ones
 };
 
 // Fork/join events order work between streams of the same device; no timing, and no system-scope
@@ -305,6 +307,12 @@ bool use_pipeline(const caramel_plan* p) {
   return 2 * uint64_t(p->host.cfg.world) * elems * p->host.elem_size() >= p->opt.pipeline_min_bytes;
 }
 
+// PER_UNIT or PER_STREAM: what the launch mode comes to for this plan.
+uint32_t effective_mode(const caramel_plan* p, bool pipelined) {
+  if (p->opt.launch_mode != CARAMEL_LAUNCH_AUTO) return p->opt.launch_mode;
+  return pipelined ? CARAMEL_LAUNCH_PER_UNIT : CARAMEL_LAUNCH_PER_STREAM;
+}
+
 const std::vector<LaunchGroup>& launch_groups(const caramel_plan* p, Binding& bd, bool direct, bool pipelined) {
   const int ti = direct ? 1 : 0;
   std::vector<LaunchGroup>& out = bd.groups[ti];
@@ -312,8 +320,7 @@ const std::vector<LaunchGroup>& launch_groups(const caramel_plan* p, Binding& bd
   out.clear();
   const TileTables& tt = bd.tt;
   const std::vector<UnitTiles>& unit_tiles = direct ? tt.direct_unit : tt.staged_unit;
-  uint32_t mode = p->opt.launch_mode;
-  if (mode == CARAMEL_LAUNCH_AUTO) mode = pipelined ? CARAMEL_LAUNCH_PER_UNIT : CARAMEL_LAUNCH_PER_STREAM;
+  const uint32_t mode = effective_mode(p, pipelined);
   const uint64_t es = p->host.elem_size();
   // Without the pipeline both plan streams run on the caller's stream: treat them as one lane.
   const uint32_t lanes = pipelined ? p->host.cfg.num_streams : 1;
@@ -355,6 +362,18 @@ const std::vector<LaunchGroup>& launch_groups(const caramel_plan* p, Binding& bd
         }
       }
     }
+  }
+  // One launch per class on one stream: if the short runs are few, their tiles (which follow the
+  // long tiles in the table) join the launch over the long tiles, whose kernel takes a tile of up
+  // to one vector per lane in a single pass.  That saves a launch of a few microseconds; the
+  // small tiles come last in the grid and fill the tail of the long ones.
+  if (mode == CARAMEL_LAUNCH_PER_STREAM && lanes == 1 && out.size() == 2 && out[0].cls == kLong &&
+      out[1].cls == kSmall && out[1].elems * es <= p->opt.merge_small_bytes &&
+      out[0].reduce.begin + out[0].reduce.count == out[1].reduce.begin &&
+      bd.shape.small_vecs <= p->opt.block) {
+    out[0].reduce.count += out[1].reduce.count;
+    out[0].elems += out[1].elems;
+    out.pop_back();
   }
   // issue in the order of the first unit, which alternates between the streams ...
   std::stable_sort(out.begin(), out.end(),
@@ -657,6 +676,11 @@ int caramel_plan_set_option(caramel_plan* p, uint32_t option, uint64_t value) {
     case CARAMEL_OPT_BLOCK:
       if (!is_block(value)) return fail(CARAMEL_EINVAL, "block must be 256, 512 or 1024");
       p->opt.block = uint32_t(value);
+      regroup();
+      return CARAMEL_OK;
+    case CARAMEL_OPT_MERGE_SMALL_BYTES:
+      p->opt.merge_small_bytes = value;
+      regroup();
       return CARAMEL_OK;
     default:
       return fail(CARAMEL_EINVAL, "unknown option %u", option);
@@ -860,6 +884,39 @@ int allreduce_static(caramel_plan* p, void* const* grads, hipStream_t stream) {
 
 int caramel_allreduce_static(caramel_plan* p, void* const* grads, void* stream) {
   return guarded([&] { return allreduce_static(p, grads, hipStream_t(stream)); });
+}
+
+int caramel_allreduce_loop(caramel_plan* p, void* stream, uint32_t n_calls, double* host_us_per_call,
+                           double* stream_us_per_call) {
+  return guarded([&]() -> int {
+    if (!host_us_per_call || !stream_us_per_call || n_calls == 0) return fail(CARAMEL_EINVAL, "NULL argument or no calls");
+    const bool direct = p && (p->opt.batch_path == CARAMEL_BATCH_DIRECT || p->host.fused_elems == 0);
+    if (int rc = need_bound(p, !direct)) return rc;
+    hipStream_t s = hipStream_t(stream);
+    hipEvent_t e0 = nullptr, e1 = nullptr;
+    HIP_TRY(hipEventCreate(&e0));
+    if (hipEventCreate(&e1) != hipSuccess) {
+      (void)hipEventDestroy(e0);
+      return fail(CARAMEL_EHIP, "hipEventCreate failed");
+    }
+    int rc = CARAMEL_OK;
+    hipError_t he = hipStreamSynchronize(s);
+    if (he == hipSuccess) he = hipEventRecord(e0, s);
+    const auto t0 = std::chrono::steady_clock::now();
+    for (uint32_t i = 0; i < n_calls && !rc && he == hipSuccess; ++i) rc = pipeline(p, s, true, direct);
+    const auto t1 = std::chrono::steady_clock::now();
+    if (he == hipSuccess) he = hipEventRecord(e1, s);
+    if (he == hipSuccess) he = hipEventSynchronize(e1);
+    float ms = 0.f;
+    if (he == hipSuccess) he = hipEventElapsedTime(&ms, e0, e1);
+    (void)hipEventDestroy(e0);
+    (void)hipEventDestroy(e1);
+    if (rc) return rc;
+    if (he != hipSuccess) return fail(CARAMEL_EHIP, "timing the loop: %s", hipGetErrorString(he));
+    *host_us_per_call = std::chrono::duration<double, std::micro>(t1 - t0).count() / n_calls;
+    *stream_us_per_call = double(ms) * 1e3 / n_calls;
+    return CARAMEL_OK;
+  });
 }
 
 int caramel_profile(caramel_plan* p, int enable) {

@@ -207,39 +207,60 @@ k_ring_reduce(const ReduceTile* __restrict__ tiles, const uint64_t* __restrict__
 }
 
 // One stream-major pass over U vectors of this lane (B apart, starting at v): the chain is walked
-// one worker at a time, with the next worker's U loads in flight while the current ones are added.
+// one worker at a time, with the loads of the next D - 1 workers in flight while the current
+// worker's values are added.  (D = 2 everywhere: looking further ahead for short tiles, which
+// have fewer vectors per lane, measured no faster.)
 // RAGGED: the last of the U vectors may lie at or beyond nvec; such a lane reads the tile's last
 // vector instead (no divergence among the loads) and stores nothing for it.
-template <int W, int U, bool BF16, bool NT, bool RAGGED>
+// TREE: the values are added as the balanced pairwise tree of the halving-doubling order instead of
+// a chain: worker k's value is merged with the open partial sums the way a binary counter carries
+// (one level per trailing one bit of k), which needs log2(W) partial sums per vector.
+template <int W, int U, int D, bool BF16, bool NT, bool RAGGED, bool TREE = false>
 __device__ __forceinline__ void sm_walk(const gvec_ptr (&p)[W], uint32_t v, uint32_t B, uint32_t nvec, float inv_w) {
-  u32x4 cur[U], nxt[U];
+  static_assert(D >= 2 && D <= W, "look-ahead between 2 and W workers");
+  static_assert(!TREE || (W & (W - 1)) == 0, "the tree needs a power of two");
+  constexpr int LEVELS = W >= 16 ? 4 : (W >= 8 ? 3 : (W >= 4 ? 2 : 1));
+  u32x4 buf[D][U];
   Chain<BF16> acc[U];
+  Chain<BF16> lvl[TREE ? LEVELS : 1][U];
   const bool last_ok = !RAGGED || v + (U - 1) * B < nvec;
   auto off = [&](int u) -> uint32_t {
     if (RAGGED && u == U - 1) return (last_ok ? v + (U - 1) * B : nvec - 1) * 16u;
     return (v + u * B) * 16u;
   };
 #pragma unroll
-  for (int u = 0; u < U; ++u) cur[u] = ld<NT>(at(p[0], off(u)));
+  for (int k = 0; k < D - 1; ++k)
 #pragma unroll
-  for (int k = 1; k < W; ++k) {
+    for (int u = 0; u < U; ++u) buf[k][u] = ld<NT>(at(p[k], off(u)));
 #pragma unroll
-    for (int u = 0; u < U; ++u) nxt[u] = ld<NT>(at(p[k], off(u)));
+  for (int k = 0; k < W; ++k) {
+    if (k + D - 1 < W) {
+#pragma unroll
+      for (int u = 0; u < U; ++u) buf[(k + D - 1) % D][u] = ld<NT>(at(p[k + D - 1], off(u)));
+    }
     __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
     for (int u = 0; u < U; ++u) {
-      if (k == 1) acc[u].start(cur[u]);
-      else acc[u].add(cur[u]);
-      cur[u] = nxt[u];
+      if constexpr (!TREE) {
+        if (k == 0) acc[u].start(buf[k % D][u]);
+        else acc[u].add(buf[k % D][u]);
+      } else {
+        acc[u].start(buf[k % D][u]);
+        int j = 0;
+#pragma unroll
+        for (int m = k; m & 1; m >>= 1) {
+          lvl[j][u].merge(acc[u]);  // the earlier partial sum + the later one
+          acc[u] = lvl[j][u];
+          ++j;
+        }
+        if (k + 1 < W) lvl[j][u] = acc[u];
+      }
     }
     __builtin_amdgcn_sched_barrier(0);
   }
   u32x4 y[U];
 #pragma unroll
-  for (int u = 0; u < U; ++u) {
-    acc[u].add(cur[u]);
-    y[u] = acc[u].finish(inv_w);
-  }
+  for (int u = 0; u < U; ++u) y[u] = acc[u].finish(inv_w);
   constexpr int SURE = RAGGED ? U - 1 : U;  // vectors that are stored by every lane
 #pragma unroll
   for (int k = 0; k < W; ++k)
@@ -320,10 +341,10 @@ k_ring_reduce_sm(const ReduceTile* __restrict__ tiles, const uint64_t* __restric
         for (int k = 0; k < W; ++k) st<NT>(at(p[k], v * 16u), y);
       }
     }
-    if (rows_left == 2) sm_walk<W, 2, BF16, NT, true>(p, v, B, nvec, inv_w);
+    if (rows_left == 2) sm_walk<W, 2, 2, BF16, NT, true>(p, v, B, nvec, inv_w);
     if constexpr (U >= 4) {
-      if (rows_left == 3) sm_walk<W, 3, BF16, NT, true>(p, v, B, nvec, inv_w);
-      if (rows_left == 4) sm_walk<W, 4, BF16, NT, true>(p, v, B, nvec, inv_w);
+      if (rows_left == 3) sm_walk<W, 3, 2, BF16, NT, true>(p, v, B, nvec, inv_w);
+      if (rows_left == 4) sm_walk<W, 4, 2, BF16, NT, true>(p, v, B, nvec, inv_w);
     }
     const uint32_t rem = tl.n_elems - nvec * VE;
     if (threadIdx.x < rem) {
@@ -346,9 +367,68 @@ k_ring_reduce_sm(const ReduceTile* __restrict__ tiles, const uint64_t* __restric
   }
 }
 
+// Stream-major kernel for the halving-doubling order (W a power of two up to 16): the same walk,
+// one replica after the other, with the values added as the balanced tree.  The tree does not
+// depend on the segment, so the workers are read in the order 0 .. W-1.
+template <int W, int U, bool BF16, bool NT>
+__global__ void __launch_bounds__(kMaxBlock)
+k_ring_reduce_smt(const ReduceTile* __restrict__ tiles, const uint64_t* __restrict__ rows, uint32_t begin,
+                  uint32_t count, float inv_w) {
+  constexpr uint32_t VE = BF16 ? 8 : 4;
+  for (uint32_t ti = blockIdx.x; ti < count; ti += gridDim.x) {
+    const ReduceTile tl = tiles[begin + ti];
+    gvec_ptr p[W];
+#pragma unroll
+    for (int k = 0; k < W; ++k) p[k] = reinterpret_cast<gvec_ptr>(rows[size_t(tl.row) * W + k]) + tl.vec_off;
+    const uint32_t nvec = tl.n_elems / VE;
+    const uint32_t B = blockDim.x;
+    const uint32_t whole = nvec / (U * B) * (U * B);  // the same for all lanes
+    uint32_t v = threadIdx.x;
+#pragma unroll 1
+    for (; v < whole; v += U * B) sm_walk<W, U, 2, BF16, NT, false, true>(p, v, B, nvec, inv_w);
+    const uint32_t rows_left = (nvec - whole + B - 1) / B;
+    if (rows_left == 1) {
+      if (v < nvec) {
+        u32x4 x[W];
+#pragma unroll
+        for (int k = 0; k < W; ++k) x[k] = ld<NT>(at(p[k], v * 16u));
+        __builtin_amdgcn_sched_barrier(0);
+        const u32x4 y = combine<W, BF16, true>(x, inv_w);
+#pragma unroll
+        for (int k = 0; k < W; ++k) st<NT>(at(p[k], v * 16u), y);
+      }
+    }
+    if (rows_left == 2) sm_walk<W, 2, 2, BF16, NT, true, true>(p, v, B, nvec, inv_w);
+    if constexpr (U >= 4) {
+      if (rows_left == 3) sm_walk<W, 3, 2, BF16, NT, true, true>(p, v, B, nvec, inv_w);
+      if (rows_left == 4) sm_walk<W, 4, 2, BF16, NT, true, true>(p, v, B, nvec, inv_w);
+    }
+    const uint32_t rem = tl.n_elems - nvec * VE;
+    if (threadIdx.x < rem) {
+      const uint32_t e = nvec * VE + threadIdx.x;
+      float val[W];
+      if constexpr (BF16) {
+#pragma unroll
+        for (int k = 0; k < W; ++k) val[k] = widen(reinterpret_cast<gu16_ptr>(p[k])[e]);
+        const uint16_t y = uint16_t(bf16_rne(combine_scalar<W, true>(val, inv_w)));
+#pragma unroll
+        for (int k = 0; k < W; ++k) reinterpret_cast<gu16_ptr>(p[k])[e] = y;
+      } else {
+#pragma unroll
+        for (int k = 0; k < W; ++k) val[k] = reinterpret_cast<gf32_ptr>(p[k])[e];
+        const float y = combine_scalar<W, true>(val, inv_w);
+#pragma unroll
+        for (int k = 0; k < W; ++k) reinterpret_cast<gf32_ptr>(p[k])[e] = y;
+      }
+    }
+  }
+}
+
 // Any W: the chain is walked one worker at a time, like the stream-major kernel: the next
-// worker's base pointer (a scalar load) and its U vectors per lane are requested while the
-// current ones are added.
+// worker's base pointer (a scalar load) and its vectors are requested while the current ones are
+// added.  What is left of a tile after whole groups of U*B vectors (up to U rows of B lanes, the
+// last row possibly ragged) is walked in one go with that many vectors per lane; a lane beyond
+// the end of a ragged row reads the tile's last vector instead and stores nothing for it.
 template <bool BF16, bool NT, int U>
 __global__ void __launch_bounds__(kMaxBlock)
 k_ring_reduce_any(const ReduceTile* __restrict__ tiles, const uint64_t* __restrict__ rows, uint32_t begin,
@@ -360,19 +440,25 @@ k_ring_reduce_any(const ReduceTile* __restrict__ tiles, const uint64_t* __restri
     const uint32_t nvec = tl.n_elems / VE;
     const uint32_t B = blockDim.x;
     // one pass of the chain over N vectors of this lane, B apart, starting at v
-    auto chain = [&](uint32_t v, auto n_tag) {
+    auto chain = [&](uint32_t v, auto n_tag, auto ragged_tag) {
       constexpr int N = decltype(n_tag)::value;
+      constexpr bool RAGGED = decltype(ragged_tag)::value;
       Chain<BF16> acc[N];
       u32x4 cur[N], nxt[N];
+      const bool last_ok = !RAGGED || v + (N - 1) * B < nvec;
+      uint32_t off[N];
+#pragma unroll
+      for (int u = 0; u < N; ++u) off[u] = (v + u * B) * 16u;
+      if (RAGGED && !last_ok) off[N - 1] = (nvec - 1) * 16u;
       uint32_t w = tl.first;
       gvec_ptr base = reinterpret_cast<gvec_ptr>(row[w]) + tl.vec_off;
 #pragma unroll
-      for (int u = 0; u < N; ++u) cur[u] = ld<NT>(at(base, (v + u * B) * 16u));
+      for (int u = 0; u < N; ++u) cur[u] = ld<NT>(at(base, off[u]));
       for (uint32_t k = 1; k < W; ++k) {
         w = (w + 1 == W) ? 0 : w + 1;
         base = reinterpret_cast<gvec_ptr>(row[w]) + tl.vec_off;
 #pragma unroll
-        for (int u = 0; u < N; ++u) nxt[u] = ld<NT>(at(base, (v + u * B) * 16u));
+        for (int u = 0; u < N; ++u) nxt[u] = ld<NT>(at(base, off[u]));
         __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
         for (int u = 0; u < N; ++u) {
@@ -392,12 +478,41 @@ k_ring_reduce_any(const ReduceTile* __restrict__ tiles, const uint64_t* __restri
       for (uint32_t k = 0; k < W; ++k) {
         base = reinterpret_cast<gvec_ptr>(row[k]) + tl.vec_off;
 #pragma unroll
-        for (int u = 0; u < N; ++u) st<NT>(at(base, (v + u * B) * 16u), y[u]);
+        for (int u = 0; u < N; ++u)
+          if (!RAGGED || u < N - 1 || last_ok) st<NT>(at(base, off[u]), y[u]);
       }
     };
+    const uint32_t whole = nvec / (U * B) * (U * B);  // the same for all lanes
     uint32_t v = threadIdx.x;
-    for (; v + (U - 1) * B < nvec; v += U * B) chain(v, std::integral_constant<int, U>{});
-    for (; v < nvec; v += B) chain(v, std::integral_constant<int, 1>{});
+    for (; v < whole; v += U * B) chain(v, std::integral_constant<int, U>{}, std::false_type{});
+    const uint32_t rows_left = (nvec - whole + B - 1) / B;
+    static_assert(U == 4, "the dispatch below lists the row counts of U = 4");
+    if (rows_left == 1 && v < nvec) {
+      // at most one vector per lane: nothing to walk; fetch the workers' values eight at a time
+      Chain<BF16> acc;
+      for (uint32_t k0 = 0; k0 < W; k0 += 8) {
+        u32x4 x[8];
+#pragma unroll
+        for (uint32_t i = 0; i < 8; ++i)
+          if (k0 + i < W) {
+            uint32_t w = tl.first + k0 + i;
+            if (w >= W) w -= W;
+            x[i] = ld<NT>(at(reinterpret_cast<gvec_ptr>(row[w]) + tl.vec_off, v * 16u));
+          }
+        __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+        for (uint32_t i = 0; i < 8; ++i)
+          if (k0 + i < W) {
+            if (k0 + i == 0) acc.start(x[i]);
+            else acc.add(x[i]);
+          }
+      }
+      const u32x4 y = acc.finish(inv_w);
+      for (uint32_t k = 0; k < W; ++k) st<NT>(at(reinterpret_cast<gvec_ptr>(row[k]) + tl.vec_off, v * 16u), y);
+    }
+    if (rows_left == 2) chain(v, std::integral_constant<int, 2>{}, std::true_type{});
+    if (rows_left == 3) chain(v, std::integral_constant<int, 3>{}, std::true_type{});
+    if (rows_left == 4) chain(v, std::integral_constant<int, 4>{}, std::true_type{});
     const uint32_t rem = tl.n_elems - nvec * VE;
     if (threadIdx.x < rem) {
       const size_t e = size_t(tl.vec_off) * VE + nvec * VE + threadIdx.x;
@@ -572,8 +687,26 @@ hipError_t launch_sm(const ReduceArgs& a, dim3 grid, float inv_w, hipStream_t s)
   return hipGetLastError();
 }
 
+// fp32: four vectors per lane; bf16 (twice the partial sums per vector): two, i.e. a long tile in
+// two passes
+template <int W>
+hipError_t launch_smt(const ReduceArgs& a, dim3 grid, float inv_w, hipStream_t s) {
+#define CARAMEL_SMT(U, BF, NT) \
+  hipLaunchKernelGGL((k_ring_reduce_smt<W, U, BF, NT>), grid, dim3(a.block), 0, s, a.tiles, a.rows, a.begin, a.count, inv_w)
+  if (a.bf16) {
+    if (a.nontemporal) CARAMEL_SMT(2, true, true); else CARAMEL_SMT(2, true, false);
+  } else if (a.stream_major >= 4) {
+    if (a.nontemporal) CARAMEL_SMT(4, false, true); else CARAMEL_SMT(4, false, false);
+  } else {
+    if (a.nontemporal) CARAMEL_SMT(2, false, true); else CARAMEL_SMT(2, false, false);
+  }
+#undef CARAMEL_SMT
+  return hipGetLastError();
+}
+
 template <int W>
 hipError_t launch_u(const ReduceArgs& a, dim3 grid, float inv_w, hipStream_t s) {
+  if (a.stream_major && a.tree) return launch_smt<W>(a, grid, inv_w, s);
   if (a.stream_major && !a.tree) {
     if (a.stream_major >= 4) return launch_sm<W, 4>(a, grid, inv_w, s);
     return launch_sm<W, 2>(a, grid, inv_w, s);

@@ -41,16 +41,23 @@ void build_tiles(const HostPlan& p, const TileShape& ts, TileTables& out, const 
   out.copy_unit.resize(nu);
   for (uint32_t ui = 0; ui < nu; ++ui) out.order[p.units[ui].stream].push_back(ui);
 
-  // Position of a row's element inside an aligned block of `block_elems` elements of memory, if
-  // it is the same in every replica (the normal case: tensors at the same offsets of equally
-  // aligned arenas); 0 otherwise, and without addresses.
+  // Position of a row's element inside an aligned block of `block_elems` elements of memory.
+  // Normally it is the same in every replica (tensors at the same offsets of equally aligned
+  // arenas); if not, the position most replicas share is taken (the first such, for a tie), so
+  // that as many replicas as possible see aligned tiles.  Without addresses: 0.
+  std::vector<uint64_t> ph(W);
   auto common_phase = [&](uint32_t row, uint64_t elem, uint64_t block_elems) -> uint64_t {
     if (!row_addr) return 0;
     const uint64_t block_b = block_elems * es;
-    const uint64_t first = (row_addr[size_t(row) * W] + elem * es) % block_b;
-    for (uint32_t w = 1; w < W; ++w)
-      if ((row_addr[size_t(row) * W + w] + elem * es) % block_b != first) return 0;
-    return first / es;
+    for (uint32_t w = 0; w < W; ++w) ph[w] = (row_addr[size_t(row) * W + w] + elem * es) % block_b;
+    uint64_t best = ph[0];
+    uint32_t best_n = 0;
+    for (uint32_t w = 0; w < W; ++w) {
+      uint32_t n = 0;
+      for (uint32_t x = 0; x < W; ++x) n += ph[x] == ph[w];
+      if (n > best_n) best = ph[w], best_n = n;
+    }
+    return best / es;
   };
 
   // The runs of a unit in one table, segment by segment.

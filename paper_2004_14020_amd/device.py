@@ -24,12 +24,14 @@ class Replicas:
     buffer of a training framework.  Tensors of at least `large_bytes` start on `large_align`
     boundaries (64 KiB: the reduce kernel's large tiles then coincide with aligned 64 KiB
     blocks of memory, which it streams measurably faster); the others on `slot_align`.
-    `arena_phase`, if given, makes every arena start at an address congruent to it modulo
-    64 KiB (a multiple of 256), so that tests can choose how runs sit relative to aligned blocks."""
+    Every arena starts at an address congruent to `arena_phase` (default 0, a multiple of 256)
+    modulo 64 KiB, so that tests can choose how runs sit relative to aligned blocks;
+    `arena_phases`, one value per replica, places the replicas differently from one another."""
 
     def __init__(self, plan: Plan, elems: Sequence[int], device: str = "cuda:0", slot_align: int = 256,
                  large_align: int = 65536, large_bytes: int = 1 << 20,
-                 with_workspace: bool = True, arena_phase: Optional[int] = None):
+                 with_workspace: bool = True, arena_phase: Optional[int] = None,
+                 arena_phases: Optional[Sequence[int]] = None):
         self.plan = plan
         self.world = plan.cfg.world
         self.elems = [int(e) for e in elems]
@@ -44,18 +46,22 @@ class Replicas:
             at += n * self.es
         self.offsets = offs
         self.arena_bytes = max(at, slot_align)
-        if arena_phase is None:
-            self.arenas = [torch.empty(self.arena_bytes, dtype=torch.uint8, device=self.device)
-                           for _ in range(self.world)]
-        else:
-            if arena_phase % 256 or not 0 <= arena_phase < 65536:
-                raise ValueError("arena_phase must be a multiple of 256 below 65536")
-            self._backing = [torch.empty(self.arena_bytes + 2 * 65536, dtype=torch.uint8, device=self.device)
-                             for _ in range(self.world)]
-            self.arenas = []
-            for b in self._backing:
-                skip = (arena_phase - b.data_ptr()) % 65536
-                self.arenas.append(b[skip:skip + self.arena_bytes])
+        # Every arena starts at the same position inside an aligned 64 KiB block (position 0 unless
+        # `arena_phase` says otherwise), as separately allocated flat buffers do; a caching
+        # allocator that carves a new tensor out of a freed larger one does not promise that, so
+        # the arenas are cut out of slightly larger tensors.
+        phase = 0 if arena_phase is None else arena_phase
+        if phase % 256 or not 0 <= phase < 65536:
+            raise ValueError("arena_phase must be a multiple of 256 below 65536")
+        self._backing = [torch.empty(self.arena_bytes + 65536, dtype=torch.uint8, device=self.device)
+                         for _ in range(self.world)]
+        self.arenas = []
+        for w, b in enumerate(self._backing):
+            ph = phase if arena_phases is None else int(arena_phases[w])
+            if ph % 256 or not 0 <= ph < 65536:
+                raise ValueError("arena phases must be multiples of 256 below 65536")
+            skip = (ph - b.data_ptr()) % 65536
+            self.arenas.append(b[skip:skip + self.arena_bytes])
         fe = plan.fused_elems
         self.fused: Optional[torch.Tensor] = None
         if with_workspace and fe > 0:

@@ -88,6 +88,9 @@ def test_allreduce_all_modes(W, dtype, launch, batch, streams):
     {cm.OPT_STREAM_MAJOR: 2, cm.OPT_LONG_RUN_BYTES: 0, cm.OPT_TILE_VECS: 512, cm.OPT_BLOCK: 256},
     {cm.OPT_STREAM_MAJOR: 4, cm.OPT_LONG_RUN_BYTES: 4096, cm.OPT_TILE_VECS: 1024, cm.OPT_BLOCK: 256, cm.OPT_BATCH_PATH: cm.BATCH_STAGED},
     {cm.OPT_LONG_RUN_BYTES: 0}, {cm.OPT_LONG_RUN_BYTES: 0, cm.OPT_STREAM_MAJOR: 0}, {cm.OPT_LONG_RUN_BYTES: 1 << 40},
+    {cm.OPT_LONG_RUN_BYTES: 4096, cm.OPT_MERGE_SMALL_BYTES: 0}, {cm.OPT_LONG_RUN_BYTES: 4096, cm.OPT_MERGE_SMALL_BYTES: 1 << 30},
+    {cm.OPT_LAUNCH_MODE: cm.LAUNCH_PER_UNIT, cm.OPT_LONG_RUN_BYTES: 4096, cm.OPT_LONG_LAUNCH_MIN_BYTES: 0},
+    {cm.OPT_LONG_RUN_BYTES: 4096, cm.OPT_MERGE_SMALL_BYTES: 1 << 30, cm.OPT_SMALL_TILE_VECS: 1024, cm.OPT_STREAM_MAJOR: 2, cm.OPT_TILE_VECS: 2048},
     {cm.OPT_LONG_RUN_BYTES: 100000, cm.OPT_SMALL_TILE_VECS: 64}, {cm.OPT_LONG_RUN_BYTES: 2048, cm.OPT_LONG_LAUNCH_MIN_BYTES: 0},
     {cm.OPT_LONG_RUN_BYTES: 65536, cm.OPT_SMALL_BLOCK: 512, cm.OPT_SMALL_TILE_VECS: 1024, cm.OPT_BATCH_PATH: cm.BATCH_STAGED},
     {cm.OPT_BLOCK: 256}, {cm.OPT_BLOCK: 1024, cm.OPT_TILE_VECS: 2048}, {cm.OPT_BLOCK: 1024, cm.OPT_TILE_VECS: 128},
@@ -164,6 +167,24 @@ def test_long_tiles_cut_on_aligned_blocks_give_the_same_bits(phase, dtype):
         plan.close()
 
 
+@pytest.mark.parametrize("dtype", [oracle.F32, oracle.BF16])
+def test_replicas_at_different_positions_inside_aligned_blocks(dtype):
+    """Replicas that disagree on where a tensor sits inside an aligned block of memory: tiles are
+    cut for the position most of them share (or for none); the bits do not depend on it."""
+    print(f"case: replicas at different phases dtype={dtype}", flush=True)
+    cfg = oracle.Config(8, dtype, 8192, oracle.SPLIT_FIXED, 8, 1 << 20, 16, 2)
+    elems = [600000, 33, 262144 + 4, 5000]
+    grads = make_inputs(cfg, elems, seed=13)
+    ref = oracle_result(cfg, elems, grads)
+    for phases in ([0, 0, 256, 0, 4096, 0, 0, 512], [256 * w for w in range(8)], [1024] * 4 + [2048] * 4):
+        plan = lib_plan(cfg, elems, {cm.OPT_LONG_RUN_BYTES: 4096})
+        dev = Replicas(plan, elems, slot_align=256, large_align=256, arena_phases=phases)
+        dev.upload(grads)
+        plan.allreduce()
+        assert_same_bits(dev.download(), ref, f"phases {phases}")
+        plan.close()
+
+
 def test_batching_off_and_single_tiny_tensor():
     for elems, T in (([1], 0), ([3, 5], 0), ([2], 1 << 20), ([5, 3, 9], 1 << 20)):
         for W in (1, 4, 16):
@@ -213,6 +234,49 @@ def test_special_values_follow_ieee():
         for w in range(W):
             assert (got[w][0][seg[c]:seg[c + 1]] == np.float32(want)).all()
     plan.close()
+
+
+def test_bf16_special_values_follow_ieee():
+    """bf16 in and out: infinities propagate, Inf - Inf and NaN inputs (quiet or signalling) give
+    a NaN (payload bits are not compared), an fp32 sum that overflows gives Inf, bf16 denormals
+    are widened, added and rounded without a flush to zero, and signed zeros keep their sign.
+    Everything that is not a NaN is compared bit for bit."""
+    W, n = 4, 72
+    cfg = oracle.Config(W, oracle.BF16, 0)
+    rows = [np.full(n, b, dtype=np.uint16) for b in (0x0001, 0x0003, 0x8001, 0x0005)]   # denormals
+    rows[0][5] = 0x7F80                       # +Inf and finite values
+    rows[1][6] = 0xFF80                       # -Inf
+    rows[2][8], rows[3][8] = 0x7F80, 0xFF80   # Inf - Inf
+    rows[0][9] = 0x7FC1                       # quiet NaN with a payload
+    rows[3][10] = 0x7F81                      # signalling NaN
+    for r in rows:
+        r[12] = 0x7F7F                        # 4 x the largest bf16: the fp32 sum overflows
+        r[13] = 0x8000                        # -0 + -0 + -0 + -0
+    rows[1][14], rows[2][14] = 0x8000, 0x0000  # mixed zeros (the others are denormals there)
+    rows[0][15], rows[1][15], rows[2][15], rows[3][15] = 0x0000, 0x8000, 0x8000, 0x0000
+    rows[0][16], rows[1][16], rows[2][16], rows[3][16] = 0x007F, 0x007F, 0x0001, 0x0001   # denormals summing to a normal
+    rows[0][17], rows[1][17], rows[2][17], rows[3][17] = 0x3F80, 0x3B80, 0x0000, 0x0000   # ties at the bf16 rounding:
+    rows[0][18], rows[1][18], rows[2][18], rows[3][18] = 0x3F80, 0x3B80, 0x3B80, 0x3B80   # one down, one up, to even
+    grads = [[r] for r in rows]
+    ref = oracle_result(cfg, [n], grads)
+    for opts in ({}, {cm.OPT_LONG_RUN_BYTES: 0}):
+        plan = lib_plan(cfg, [n], opts)
+        dev = Replicas(plan, [n])
+        dev.upload(grads)
+        plan.allreduce()
+        got = dev.download()
+        plan.close()
+        want = ref[0][0]
+        is_nan = ((want & 0x7F80) == 0x7F80) & ((want & 0x007F) != 0)
+        assert is_nan[[8, 9, 10]].all() and is_nan.sum() == 3
+        for w in range(W):
+            g = got[w][0]
+            assert (((g & 0x7F80) == 0x7F80) & ((g & 0x007F) != 0))[is_nan].all(), "NaN in, NaN out"
+            assert np.array_equal(g[~is_nan], want[~is_nan])
+        g = got[0][0]
+        assert g[5] == 0x7F80 and g[6] == 0xFF80 and g[12] == 0x7F80 and g[13] == 0x8000 and g[15] == 0x0000
+        assert g[0] == 0x0002                     # (1 + 3 - 1 + 5) / 4 denormal units
+        assert g[17] == 0x3E80 and g[18] == 0x3E82
 
 
 def test_repeated_calls_are_race_free_and_idempotent_on_the_result():
@@ -288,9 +352,16 @@ def test_profile_counters():
     plan.profile(1)
     plan.allreduce()
     st = plan.profile_read()
-    assert st[cm.K_REDUCE]["launches"] == 1 and st[cm.K_REDUCE_SMALL]["launches"] == 1      # AUTO: one per class
-    assert st[cm.K_REDUCE]["elements"] + st[cm.K_REDUCE_SMALL]["elements"] == sum(elems)   # in place: no padding
-    assert st[cm.K_REDUCE]["elements"] > 0
+    # AUTO: one launch per class on the caller's stream, and the few small tiles join the long ones
+    assert st[cm.K_REDUCE]["launches"] == 1 and st[cm.K_REDUCE_SMALL]["launches"] == 0
+    assert st[cm.K_REDUCE]["elements"] == sum(elems)                                      # in place: no padding
+    plan.set_option(cm.OPT_MERGE_SMALL_BYTES, 0)
+    plan.profile(1)
+    plan.allreduce()
+    st = plan.profile_read()
+    assert st[cm.K_REDUCE]["launches"] == 1 and st[cm.K_REDUCE_SMALL]["launches"] == 1
+    assert st[cm.K_REDUCE]["elements"] + st[cm.K_REDUCE_SMALL]["elements"] == sum(elems)
+    assert st[cm.K_REDUCE]["elements"] > 0 and st[cm.K_REDUCE_SMALL]["elements"] > 0
     plan.profile(0)
     plan.close()
 

@@ -43,6 +43,7 @@ def draw(rng: random.Random):
             cm.OPT_LONG_RUN_BYTES: rng.choice([0, 1024, 32768, 32768, 1 << 40]),
             cm.OPT_LONG_LAUNCH_MIN_BYTES: rng.choice([0, 200000, 64 << 20]),
             cm.OPT_STREAM_MAJOR: rng.choice([0, 2, 4]),
+            cm.OPT_MERGE_SMALL_BYTES: rng.choice([0, 1 << 20, 1 << 40]),
             cm.OPT_ALIGN_TILES: rng.choice([0, 1, 2, 3]),
             cm.OPT_LAUNCH_MIN_BYTES: rng.choice([0, 65536, 4 << 20]),
             cm.OPT_NONTEMPORAL: rng.choice([0, 1]),

@@ -18,16 +18,21 @@ def cfg_of(wl):
                          wl.split_bytes, wl.align_bytes, wl.num_streams)
 
 
-@pytest.mark.parametrize("name,seeds", [("mlp", (0, 1, 200414020)), ("resnet50", (0, 1, 200414020)),
-                                        ("inception_v3", (0, 1)), ("vgg16", (0,)), ("transformer", (0,)),
-                                        ("alexnet_v2", (0,)), ("resnet_v2_152", (0,))])
-def test_workload_bit_exact(name, seeds):
+SEEDS = (0, 1, 200414020)
+
+
+@pytest.mark.parametrize("name,seeds", [("mlp", SEEDS), ("resnet50", SEEDS), ("inception_v3", SEEDS), ("vgg16", SEEDS),
+                                        ("transformer", SEEDS), ("alexnet_v2", (0,)), ("resnet_v2_152", (0,))])
+@pytest.mark.parametrize("large_align", [256])
+def test_workload_bit_exact(name, seeds, large_align):
+    """Default launch options, tensors placed as bench.py places them (large tensors on 256-byte
+    boundaries: tiles are cut on aligned blocks, with short first and last tiles)."""
     wl = workload(name)
     cfg = cfg_of(wl)
     elems = wl.elems()
     oplan = oracle.build_plan(cfg, elems)
     plan = lib_plan(cfg, elems)
-    dev = Replicas(plan, elems)
+    dev = Replicas(plan, elems, large_align=large_align)
     for seed in seeds:
         print(f"case: workload {name} seed {seed}: generating", flush=True)
         grads = make_inputs(cfg, elems, seed)
@@ -49,6 +54,25 @@ def test_workload_bit_exact(name, seeds):
             slack = 2.0 ** -8 * np.abs(mean[t]) if cfg.dtype == oracle.BF16 else 0.0
             assert (np.abs(y - mean[t]) <= 4e-7 * mag[t] + slack).all()
         del grads, got
+    plan.close()
+
+
+@pytest.mark.parametrize("name", ["vgg16", "transformer"])
+def test_workload_bit_exact_with_the_two_stream_pipeline_and_aligned_tensors(name):
+    """The two-stream pipeline (units alternating over the caller's and the internal stream,
+    launches of at least 64 MiB) on tensors that start on 64 KiB boundaries."""
+    wl = workload(name)
+    cfg = cfg_of(wl)
+    elems = wl.elems()
+    print(f"case: workload {name} pipelined: generating", flush=True)
+    grads = make_inputs(cfg, elems, 3)
+    plan = lib_plan(cfg, elems, {cm.OPT_LAUNCH_MODE: cm.LAUNCH_PER_UNIT})
+    dev = Replicas(plan, elems, large_align=65536)
+    dev.upload(grads)
+    plan.allreduce()
+    got = dev.download()
+    oracle.allreduce(oracle.build_plan(cfg, elems), grads)
+    assert_same_bits(got, grads, f"{name} pipelined")
     plan.close()
 
 
