@@ -40,7 +40,7 @@ def parse_args():
     ap.add_argument("--launch-min-bytes", type=int, default=None)
     ap.add_argument("--align-tiles", type=int, default=None, help="0..3, see CARAMEL_OPT_ALIGN_TILES")
     ap.add_argument("--long-run-bytes", type=int, default=None, help="see CARAMEL_OPT_LONG_RUN_BYTES")
-    ap.add_argument("--large-align", type=int, default=65536,
+    ap.add_argument("--large-align", type=int, default=256,
                     help="start of every tensor of >= 1 MiB inside a replica's arena (a multiple of 256)")
     ap.add_argument("--device-fill", action="store_true",
                     help="fill the replicas on the device instead of uploading Philox samples")

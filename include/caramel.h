@@ -314,7 +314,9 @@ enum {
    * without materialising the fused buffer (same segments, same order, same bits).
    * Default DIRECT. */
   CARAMEL_OPT_BATCH_PATH = 1,
-  /* 16-byte vectors per replica in a long tile.  Default 4096 (64 KiB). */
+  /* 16-byte vectors per replica in a long tile.  Default 0 = chosen at caramel_bind: 8192
+   * (128 KiB) for fp32 ring or shuffle sums over 2, 4 or 8 workers (the kernel can keep eight
+   * vectors per lane in registers then) once a replica holds 64 MiB; 4096 (64 KiB) otherwise. */
   CARAMEL_OPT_TILE_VECS = 2,
   /* Upper bound on workgroups per reduce launch (0 = one workgroup per tile). */
   CARAMEL_OPT_MAX_GRID = 3,
@@ -337,13 +339,15 @@ enum {
   /* Vectors per small tile and lanes per workgroup over small tiles.  Defaults 256 and 256. */
   CARAMEL_OPT_SMALL_TILE_VECS = 9,
   CARAMEL_OPT_SMALL_BLOCK = 10,
-  /* Bytes per replica from which a run is cut into long tiles.  Default 32 KiB.  0: every run is
-   * long; a huge value: every run is small. */
+  /* Bytes per replica from which a run is cut into long tiles.  Default 0 = chosen at
+   * caramel_bind: 16 KiB, or, if a replica holds less than 32 MiB in all, no long tiles at all
+   * (so small a job is over before the one-replica-at-a-time walk of a long tile pays off).
+   * 1: every run is long; a huge value: every run is small. */
   CARAMEL_OPT_LONG_RUN_BYTES = 11,
-  /* Long tiles: 2 or 4 (default) selects the stream-major kernel, which walks the chain of
-   * workers one replica at a time with that many vectors per lane (long contiguous requests per
-   * replica; meant for tiles of block * value vectors); 0 fetches all workers' values at once.
-   * The halving-doubling pattern always uses the latter. */
+  /* Long tiles: non-zero selects the stream-major kernel, which walks the workers one replica at
+   * a time; the value (2, 4 or 8, default 8) is the most vectors a lane keeps per worker: a tile
+   * of block * value vectors is walked in one go (8 exists for fp32 chains of at most 8 workers;
+   * otherwise 4 is used).  0 fetches all workers' values at once. */
   CARAMEL_OPT_STREAM_MAJOR = 12,
   /* PER_UNIT launches over long tiles: like CARAMEL_OPT_LAUNCH_MIN_BYTES.  Default 64 MiB. */
   CARAMEL_OPT_LONG_LAUNCH_MIN_BYTES = 13,
@@ -356,7 +360,13 @@ enum {
    * does): if the small tiles cover at most this many bytes per replica, they join the launch
    * over the long tiles instead of getting a launch of their own.  Default 1 MiB; 0 keeps the
    * two launches apart. */
-  CARAMEL_OPT_MERGE_SMALL_BYTES = 15
+  CARAMEL_OPT_MERGE_SMALL_BYTES = 15,
+  /* The last so many long tiles of every plan stream are cut into pieces of one vector per lane
+   * (16 KiB for 1024 lanes), which a workgroup fetches from all replicas at once.  When a launch
+   * runs out of tiles, the workgroups still at work finish at different times; with short pieces
+   * at the end that drain is short.  Default 256 (one per compute unit); 0 switches it off.
+   * Takes effect at the next caramel_bind. */
+  CARAMEL_OPT_TAIL_TILES = 16
 };
 enum { CARAMEL_LAUNCH_PER_UNIT = 0, CARAMEL_LAUNCH_PER_STREAM = 1, CARAMEL_LAUNCH_AUTO = 2 };
 enum { CARAMEL_BATCH_STAGED = 0, CARAMEL_BATCH_DIRECT = 1 };

@@ -67,7 +67,7 @@ struct Options {
   uint32_t unroll = 0;
   uint32_t block = 1024;        // workgroup of launches over long tiles
   uint32_t small_block = 256;   // ... over small tiles
-  uint32_t stream_major = 4;    // vectors per lane of the stream-major kernel for long tiles (0 = off)
+  uint32_t stream_major = 8;    // most vectors per lane of the stream-major kernel for long tiles (0 = off)
   uint64_t launch_min_bytes = 4u << 20;        // launches over small tiles: units share one up to this size
   uint64_t long_launch_min_bytes = 64u << 20;  // launches over long tiles likewise
   uint64_t pipeline_min_bytes = ~uint64_t(0);  // AUTO never pipelines unless told to
@@ -237,7 +237,12 @@ int run_reduce(caramel_plan* p, const Binding& bd, const DeviceTables& dt, bool 
   a.block = lng ? p->opt.block : p->opt.small_block;
   const uint32_t tile_vecs = lng ? bd.shape.long_vecs : bd.shape.small_vecs;
   a.unroll = p->opt.unroll ? p->opt.unroll : std::max(1u, tile_vecs / a.block);
-  a.stream_major = lng ? p->opt.stream_major : 0;
+  // stream-major walk: as many vectors per lane as a whole tile has rows of lanes (2, 4 or 8)
+  a.stream_major = 0;
+  if (lng && p->opt.stream_major) {
+    const uint32_t rows = tile_vecs / a.block;
+    a.stream_major = std::min(p->opt.stream_major, rows >= 8 ? 8u : (rows >= 4 ? 4u : 2u));
+  }
   a.max_grid = p->opt.max_grid;
   if (!timed) {
     HIP_TRY(launch_ring_reduce(a, s));
@@ -624,7 +629,7 @@ int caramel_plan_set_option(caramel_plan* p, uint32_t option, uint64_t value) {
       p->opt.batch_path = uint32_t(value);
       return CARAMEL_OK;
     case CARAMEL_OPT_TILE_VECS:
-      if (value < 64 || value > (1u << 20)) return fail(CARAMEL_EINVAL, "tile_vecs must be in [64, 2^20]");
+      if (value != 0 && (value < 64 || value > (1u << 20))) return fail(CARAMEL_EINVAL, "tile_vecs must be 0 or in [64, 2^20]");
       p->opt.shape.long_vecs = uint32_t(value);
       p->fixed_valid = false;
       return CARAMEL_OK;
@@ -642,7 +647,7 @@ int caramel_plan_set_option(caramel_plan* p, uint32_t option, uint64_t value) {
       regroup();
       return CARAMEL_OK;
     case CARAMEL_OPT_STREAM_MAJOR:
-      if (value != 0 && value != 2 && value != 4) return fail(CARAMEL_EINVAL, "stream_major must be 0, 2 or 4");
+      if (value != 0 && value != 2 && value != 4 && value != 8) return fail(CARAMEL_EINVAL, "stream_major must be 0, 2, 4 or 8");
       p->opt.stream_major = uint32_t(value);
       return CARAMEL_OK;
     case CARAMEL_OPT_ALIGN_TILES:
@@ -677,6 +682,11 @@ int caramel_plan_set_option(caramel_plan* p, uint32_t option, uint64_t value) {
       if (!is_block(value)) return fail(CARAMEL_EINVAL, "block must be 256, 512 or 1024");
       p->opt.block = uint32_t(value);
       regroup();
+      return CARAMEL_OK;
+    case CARAMEL_OPT_TAIL_TILES:
+      if (value > 0x7FFFFFFFu) return fail(CARAMEL_EINVAL, "tail_tiles too large");
+      p->opt.shape.tail_tiles = uint32_t(value);
+      p->fixed_valid = false;
       return CARAMEL_OK;
     case CARAMEL_OPT_MERGE_SMALL_BYTES:
       p->opt.merge_small_bytes = value;
@@ -733,6 +743,24 @@ int check_pointers(const HostPlan& h, void* const* grads, void* fused_ws, std::v
 
 void fill_binding(const caramel_plan* p, std::vector<uint64_t>&& rows, Binding& bd) {
   bd.shape = p->opt.shape;
+  // Shapes left to the library (option value 0) follow the size of the job, measured on MI355X:
+  //  * a replica of less than 32 MiB is done before long tiles pay off (a 1024-lane workgroup
+  //    walks its tile one replica after the other): every run is cut into small tiles, whose
+  //    workgroups fetch all replicas at once (the MLP configuration: 3.4 against 6.3 us);
+  //  * fp32 chains of 2, 4 or 8 workers, for which the kernel can keep eight vectors per lane in
+  //    registers, get long tiles of 128 KiB once a replica holds 64 MiB (VGG-16 +2 %); everything
+  //    else 64 KiB.
+  bd.shape.tail_vecs = p->opt.block;  // one vector per lane: a piece is fetched from all replicas at once
+  const caramel_config& c = p->host.cfg;
+  uint64_t replica_bytes = 0;
+  for (uint64_t e : p->host.tensor_elems) replica_bytes += e * p->host.elem_size();
+  if (bd.shape.long_run_bytes == 0) bd.shape.long_run_bytes = replica_bytes < (32u << 20) ? ~uint64_t(0) : 16u << 10;
+  if (bd.shape.long_vecs == 0) {
+    const bool wide = c.dtype == CARAMEL_F32 && c.pattern != CARAMEL_PATTERN_HALVING_DOUBLING &&
+                      (c.world == 2 || c.world == 4 || c.world == 8) && p->opt.stream_major >= 8 &&
+                      p->opt.block == 1024 && replica_bytes >= (64u << 20);
+    bd.shape.long_vecs = wide ? 8192 : 4096;
+  }
   bd.rows = std::move(rows);
   build_tiles(p->host, bd.shape, bd.tt, bd.rows.data());
   bd.groups_stale[0] = bd.groups_stale[1] = true;

@@ -346,6 +346,12 @@ k_ring_reduce_sm(const ReduceTile* __restrict__ tiles, const uint64_t* __restric
       if (rows_left == 3) sm_walk<W, 3, 2, BF16, NT, true>(p, v, B, nvec, inv_w);
       if (rows_left == 4) sm_walk<W, 4, 2, BF16, NT, true>(p, v, B, nvec, inv_w);
     }
+    if constexpr (U >= 8) {
+      if (rows_left == 5) sm_walk<W, 5, 2, BF16, NT, true>(p, v, B, nvec, inv_w);
+      if (rows_left == 6) sm_walk<W, 6, 2, BF16, NT, true>(p, v, B, nvec, inv_w);
+      if (rows_left == 7) sm_walk<W, 7, 2, BF16, NT, true>(p, v, B, nvec, inv_w);
+      if (rows_left == 8) sm_walk<W, 8, 2, BF16, NT, true>(p, v, B, nvec, inv_w);
+    }
     const uint32_t rem = tl.n_elems - nvec * VE;
     if (threadIdx.x < rem) {
       const uint32_t e = nvec * VE + threadIdx.x;
@@ -678,7 +684,11 @@ template <int W, int U>
 hipError_t launch_sm(const ReduceArgs& a, dim3 grid, float inv_w, hipStream_t s) {
 #define CARAMEL_SM(BF, NT) \
   hipLaunchKernelGGL((k_ring_reduce_sm<W, U, BF, NT>), grid, dim3(a.block), 0, s, a.tiles, a.rows, a.begin, a.count, inv_w)
-  if (a.bf16) {
+  if constexpr (U >= 8) {
+    // eight vectors per lane fit the register file for fp32 only (launch_u sends bf16 elsewhere)
+    if (a.bf16) return hipErrorInvalidValue;
+    if (a.nontemporal) CARAMEL_SM(false, true); else CARAMEL_SM(false, false);
+  } else if (a.bf16) {
     if (a.nontemporal) CARAMEL_SM(true, true); else CARAMEL_SM(true, false);
   } else {
     if (a.nontemporal) CARAMEL_SM(false, true); else CARAMEL_SM(false, false);
@@ -708,6 +718,9 @@ template <int W>
 hipError_t launch_u(const ReduceArgs& a, dim3 grid, float inv_w, hipStream_t s) {
   if (a.stream_major && a.tree) return launch_smt<W>(a, grid, inv_w, s);
   if (a.stream_major && !a.tree) {
+    if constexpr (W <= 8) {
+      if (a.stream_major >= 8 && !a.bf16) return launch_sm<W, 8>(a, grid, inv_w, s);
+    }
     if (a.stream_major >= 4) return launch_sm<W, 4>(a, grid, inv_w, s);
     return launch_sm<W, 2>(a, grid, inv_w, s);
   }

@@ -18,8 +18,9 @@ struct ReduceArgs {
   uint32_t unroll;    // vectors in flight per lane and worker: 1, 2 or 4 (0 = choose from W)
   uint32_t max_grid;  // 0 = one workgroup per tile
   uint32_t block;     // lanes per workgroup: 256, 512 or 1024
-  uint32_t stream_major;  // 0: fetch all workers at once; 2 or 4: walk the chain worker by worker,
-                          // that many vectors per lane (chain orders only)
+  uint32_t stream_major;  // 0: fetch all workers at once; 2, 4 or 8: walk the workers one by one with
+                          // (up to) that many vectors per lane; 8 exists for fp32 chains of at most
+                          // 8 workers, everything else gets 4
 };
 
 struct CopyArgs {

@@ -13,8 +13,10 @@ struct Run {
 // Cut a run into tiles of `tile_elems`.  `phase_elems` is the position of the run's start
 // inside a tile-sized block of memory (0 if unknown or not to be used): the first tile is
 // shortened so that every later tile starts on a multiple of the tile size in memory.
+// `phases`, if given, receives for every tile the position of its start inside a tile-sized
+// block (the given phase for the first tile, 0 for the others).
 void cut_run(std::vector<ReduceTile>& out, const Run& r, uint64_t vec_elems, uint64_t tile_elems,
-             uint64_t phase_elems) {
+             uint64_t phase_elems, std::vector<uint64_t>* phases = nullptr) {
   uint64_t len = phase_elems ? tile_elems - phase_elems : tile_elems;
   for (uint64_t at = 0; at < r.n; at += len, len = tile_elems) {
     ReduceTile t;
@@ -23,7 +25,49 @@ void cut_run(std::vector<ReduceTile>& out, const Run& r, uint64_t vec_elems, uin
     t.vec_off = uint32_t((r.row_elem + at) / vec_elems);
     t.n_elems = uint32_t(std::min(len, r.n - at));
     out.push_back(t);
+    if (phases) phases->push_back(at == 0 ? phase_elems : 0);
   }
+}
+
+// Cut the last `n_tail` tiles of tiles[begin..] into pieces of at most `piece_elems` elements
+// (pieces of a tile stay where the tile was, in order) and move the tile ranges of the units
+// along.  phases[i - begin] is the position of tile i's start inside a tile-sized block of
+// memory; if the piece size divides the tile size, pieces are cut on multiples of the piece size
+// in memory (the first piece of a tile that starts inside such a block is shortened).
+void split_tail(std::vector<ReduceTile>& tiles, size_t begin, const std::vector<uint64_t>& phases, uint32_t n_tail,
+                uint64_t piece_elems, bool align_pieces, uint64_t vec_elems, std::vector<UnitTiles>& per_unit,
+                const std::vector<uint32_t>& units) {
+  const size_t n = tiles.size() - begin;
+  if (n == 0) return;
+  const size_t first = begin + (n > n_tail ? n - n_tail : 0);
+  std::vector<ReduceTile> cut;
+  std::vector<uint32_t> grew(tiles.size() - first, 0);  // pieces added per original tile
+  for (size_t i = first; i < tiles.size(); ++i) {
+    const ReduceTile& t = tiles[i];
+    uint32_t pieces = 0;
+    const uint64_t ph = align_pieces ? phases[i - begin] % piece_elems : 0;
+    uint64_t len = ph ? piece_elems - ph : piece_elems;
+    for (uint64_t at = 0; at < t.n_elems; at += len, len = piece_elems, ++pieces) {
+      ReduceTile q = t;
+      q.vec_off = uint32_t(t.vec_off + at / vec_elems);
+      q.n_elems = uint32_t(std::min<uint64_t>(len, t.n_elems - at));
+      cut.push_back(q);
+    }
+    grew[i - first] = pieces - 1;
+  }
+  // unit ranges: a unit's begin moves by the pieces added before it, its count by those inside
+  for (uint32_t u : units) {
+    Range& r = per_unit[u].tiles[kLong];
+    uint32_t before = 0, inside = 0;
+    for (size_t i = first; i < tiles.size(); ++i) {
+      if (i < r.begin) before += grew[i - first];
+      else if (i < size_t(r.begin) + r.count) inside += grew[i - first];
+    }
+    r.begin += before;
+    r.count += inside;
+  }
+  tiles.resize(first);
+  tiles.insert(tiles.end(), cut.begin(), cut.end());
 }
 
 }  // namespace
@@ -94,18 +138,24 @@ void build_tiles(const HostPlan& p, const TileShape& ts, TileTables& out, const 
     for (int cls = 0; cls < 2; ++cls) {
       const uint64_t tile_elems = uint64_t(cls == kLong ? ts.long_vecs : ts.small_vecs) * ve;
       const bool align = (ts.align_tiles & (cls == kSmall ? 1u : 2u)) != 0;
-      for (uint32_t s = 0; s < p.cfg.num_streams; ++s)
+      for (uint32_t s = 0; s < p.cfg.num_streams; ++s) {
+        const size_t stream_begin = tiles.size();
+        std::vector<uint64_t> phases;
         for (uint32_t ui : out.order[s]) {
           unit_runs(ui, direct);
           UnitTiles& ut = per_unit[ui];
           ut.tiles[cls].begin = uint32_t(tiles.size());
           for (const Run& r : runs) {
             if ((r.n * es >= ts.long_run_bytes) != (cls == kLong)) continue;
-            cut_run(tiles, r, ve, tile_elems, align ? common_phase(r.row, r.row_elem, tile_elems) : 0);
+            cut_run(tiles, r, ve, tile_elems, align ? common_phase(r.row, r.row_elem, tile_elems) : 0, &phases);
             ut.elems[cls] += r.n;
           }
           ut.tiles[cls].count = uint32_t(tiles.size()) - ut.tiles[cls].begin;
         }
+        if (cls == kLong && ts.tail_tiles && ts.tail_vecs && ts.tail_vecs < ts.long_vecs)
+          split_tail(tiles, stream_begin, phases, ts.tail_tiles, uint64_t(ts.tail_vecs) * ve,
+                     align && ts.long_vecs % ts.tail_vecs == 0, ve, per_unit, out.order[s]);
+      }
     }
   }
 

@@ -39,17 +39,23 @@ struct Range {
 // walk the replicas one after the other; the rest into small tiles, for 256-lane workgroups
 // that fetch all replicas at once.
 struct TileShape {
-  uint32_t long_vecs = 4096;           // vectors per long tile (64 KiB per replica)
+  uint32_t long_vecs = 0;              // vectors per long tile; 0 (options only) = chosen at bind: 4096 or 8192
   uint32_t small_vecs = 256;           // vectors per small tile
-  uint64_t long_run_bytes = 16u << 10;  // a run of at least this many bytes per replica is long
+  uint64_t long_run_bytes = 0;         // a run of at least this many bytes per replica is long; 0 (options only) = chosen at bind
   uint32_t copy_vecs = 512;            // vectors per copy tile
   // Where every replica of a run has the same address modulo the tile size, the first tile of
   // the run is shortened so that all later ones start on multiples of the tile size in memory
   // (bit 0: small tiles, bit 1: long tiles).
   uint32_t align_tiles = 3;
+  // The last `tail_tiles` long tiles of every stream are cut into pieces of `tail_vecs` vectors:
+  // when a launch runs out of tiles the workgroups still at work finish at different times, and
+  // with short pieces at the end that drain is short.
+  uint32_t tail_tiles = 256;
+  uint32_t tail_vecs = 1024;
 };
 
 enum { kLong = 0, kSmall = 1 };
+
 
 struct UnitTiles {
   Range tiles[2];                // [class] range in the table

@@ -24,8 +24,8 @@ class Replicas:
     buffer of a training framework.  Tensors of at least `large_bytes` start on `large_align`
     boundaries (64 KiB: the reduce kernel's large tiles then coincide with aligned 64 KiB
     blocks of memory, which it streams measurably faster); the others on `slot_align`.
-    Every arena starts at an address congruent to `arena_phase` (default 0, a multiple of 256)
-    modulo 64 KiB, so that tests can choose how runs sit relative to aligned blocks;
+    Every arena starts at an address congruent to `arena_phase` (default 0, a multiple of 256
+    below 64 KiB) modulo 2 MiB, so that tests can choose how runs sit relative to aligned blocks;
     `arena_phases`, one value per replica, places the replicas differently from one another."""
 
     def __init__(self, plan: Plan, elems: Sequence[int], device: str = "cuda:0", slot_align: int = 256,
@@ -46,21 +46,22 @@ class Replicas:
             at += n * self.es
         self.offsets = offs
         self.arena_bytes = max(at, slot_align)
-        # Every arena starts at the same position inside an aligned 64 KiB block (position 0 unless
+        # Every arena starts at the same position inside an aligned 2 MiB block (position 0 unless
         # `arena_phase` says otherwise), as separately allocated flat buffers do; a caching
         # allocator that carves a new tensor out of a freed larger one does not promise that, so
         # the arenas are cut out of slightly larger tensors.
         phase = 0 if arena_phase is None else arena_phase
         if phase % 256 or not 0 <= phase < 65536:
             raise ValueError("arena_phase must be a multiple of 256 below 65536")
-        self._backing = [torch.empty(self.arena_bytes + 65536, dtype=torch.uint8, device=self.device)
+        block = 2 << 20
+        self._backing = [torch.empty(self.arena_bytes + block, dtype=torch.uint8, device=self.device)
                          for _ in range(self.world)]
         self.arenas = []
         for w, b in enumerate(self._backing):
             ph = phase if arena_phases is None else int(arena_phases[w])
             if ph % 256 or not 0 <= ph < 65536:
                 raise ValueError("arena phases must be multiples of 256 below 65536")
-            skip = (ph - b.data_ptr()) % 65536
+            skip = (ph - b.data_ptr()) % block
             self.arenas.append(b[skip:skip + self.arena_bytes])
         fe = plan.fused_elems
         self.fused: Optional[torch.Tensor] = None

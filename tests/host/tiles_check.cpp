@@ -40,6 +40,8 @@ static void check_case(const caramel_config& cfg, const std::vector<uint64_t>& e
   shape.long_run_bytes = long_run_bytes;
   shape.copy_vecs = copy_vecs;
   shape.align_tiles = uint32_t(addr_seed >> 8) & 3u;
+  shape.tail_tiles = (addr_seed >> 10) & 1 ? 0 : uint32_t(1 + (addr_seed >> 11) % 40);
+  shape.tail_vecs = (addr_seed >> 17) & 1 ? 64 : 16;
   // addr_seed 0: no addresses (tiles start where runs start).  Otherwise made-up base addresses,
   // aligned as bind demands; odd seeds give every replica the same position inside a tile-sized
   // block (tiles must then start on multiples of the tile size), even seeds different ones.
@@ -135,7 +137,9 @@ static void check_case(const caramel_config& cfg, const std::vector<uint64_t>& e
           if ((addr_seed & 1) && (shape.align_tiles & (cls == kLong ? 2u : 1u))) {
             // same phase in every replica: a tile that does not begin its run begins an aligned block
             const bool continues = i > r.begin && prev_row == t.row && prev_end == e0 && prev_seg == c;
-            if (continues) CHECK((addr[size_t(t.row) * W] + e0 * es) % (cap * 16) == 0);
+            // (pieces of the tiles cut up at the end of a stream start on multiples of the piece size)
+            const uint64_t block = cls == kLong && shape.tail_tiles ? std::min<uint64_t>(cap, shape.tail_vecs) : cap;
+            if (continues) CHECK((addr[size_t(t.row) * W] + e0 * es) % (block * 16) == 0);
           }
           prev_row = t.row;
           prev_end = e1;

@@ -84,10 +84,12 @@ def test_allreduce_all_modes(W, dtype, launch, batch, streams):
     {cm.OPT_MAX_GRID: 7}, {cm.OPT_NONTEMPORAL: 0}, {cm.OPT_UNROLL: 2, cm.OPT_MAX_GRID: 300},
     {cm.OPT_LAUNCH_MIN_BYTES: 1 << 16}, {cm.OPT_LAUNCH_MIN_BYTES: 1 << 30, cm.OPT_BATCH_PATH: cm.BATCH_STAGED},
     {cm.OPT_LAUNCH_MIN_BYTES: 200000, cm.OPT_BATCH_PATH: cm.BATCH_STAGED},
-    {cm.OPT_STREAM_MAJOR: 4, cm.OPT_LONG_RUN_BYTES: 0, cm.OPT_TILE_VECS: 4096},
-    {cm.OPT_STREAM_MAJOR: 2, cm.OPT_LONG_RUN_BYTES: 0, cm.OPT_TILE_VECS: 512, cm.OPT_BLOCK: 256},
+    {cm.OPT_STREAM_MAJOR: 4, cm.OPT_LONG_RUN_BYTES: 1, cm.OPT_TILE_VECS: 4096}, {cm.OPT_LONG_RUN_BYTES: 1, cm.OPT_TILE_VECS: 8192},
+    {cm.OPT_STREAM_MAJOR: 4, cm.OPT_LONG_RUN_BYTES: 1, cm.OPT_TILE_VECS: 8192}, {cm.OPT_STREAM_MAJOR: 8, cm.OPT_LONG_RUN_BYTES: 1, cm.OPT_TILE_VECS: 2048, cm.OPT_BLOCK: 256},
+    {cm.OPT_STREAM_MAJOR: 2, cm.OPT_LONG_RUN_BYTES: 1, cm.OPT_TILE_VECS: 512, cm.OPT_BLOCK: 256},
     {cm.OPT_STREAM_MAJOR: 4, cm.OPT_LONG_RUN_BYTES: 4096, cm.OPT_TILE_VECS: 1024, cm.OPT_BLOCK: 256, cm.OPT_BATCH_PATH: cm.BATCH_STAGED},
-    {cm.OPT_LONG_RUN_BYTES: 0}, {cm.OPT_LONG_RUN_BYTES: 0, cm.OPT_STREAM_MAJOR: 0}, {cm.OPT_LONG_RUN_BYTES: 1 << 40},
+    {cm.OPT_LONG_RUN_BYTES: 1}, {cm.OPT_LONG_RUN_BYTES: 1, cm.OPT_STREAM_MAJOR: 0}, {cm.OPT_LONG_RUN_BYTES: 1 << 40},
+    {cm.OPT_LONG_RUN_BYTES: 4096, cm.OPT_TAIL_TILES: 0}, {cm.OPT_LONG_RUN_BYTES: 1, cm.OPT_TAIL_TILES: 5, cm.OPT_TILE_VECS: 2048, cm.OPT_BLOCK: 256},
     {cm.OPT_LONG_RUN_BYTES: 4096, cm.OPT_MERGE_SMALL_BYTES: 0}, {cm.OPT_LONG_RUN_BYTES: 4096, cm.OPT_MERGE_SMALL_BYTES: 1 << 30},
     {cm.OPT_LAUNCH_MODE: cm.LAUNCH_PER_UNIT, cm.OPT_LONG_RUN_BYTES: 4096, cm.OPT_LONG_LAUNCH_MIN_BYTES: 0},
     {cm.OPT_LONG_RUN_BYTES: 4096, cm.OPT_MERGE_SMALL_BYTES: 1 << 30, cm.OPT_SMALL_TILE_VECS: 1024, cm.OPT_STREAM_MAJOR: 2, cm.OPT_TILE_VECS: 2048},
@@ -157,7 +159,7 @@ def test_long_tiles_cut_on_aligned_blocks_give_the_same_bits(phase, dtype):
     elems = [600000, 33, 262144 + 4, 5000, 1 << 20]
     grads = make_inputs(cfg, elems, seed=12)
     ref = oracle_result(cfg, elems, grads)
-    for tile, block, sm in ((4096, 1024, 4), (1024, 256, 4), (2048, 1024, 2)):
+    for tile, block, sm in ((4096, 1024, 4), (1024, 256, 4), (2048, 1024, 2), (8192, 1024, 8), (0, 1024, 8), (2048, 256, 8)):
         plan = lib_plan(cfg, elems, {cm.OPT_LONG_RUN_BYTES: 4096,
                                      cm.OPT_TILE_VECS: tile, cm.OPT_BLOCK: block, cm.OPT_STREAM_MAJOR: sm})
         dev = Replicas(plan, elems, slot_align=256, large_align=256, arena_phase=phase)
@@ -259,7 +261,7 @@ def test_bf16_special_values_follow_ieee():
     rows[0][18], rows[1][18], rows[2][18], rows[3][18] = 0x3F80, 0x3B80, 0x3B80, 0x3B80   # one down, one up, to even
     grads = [[r] for r in rows]
     ref = oracle_result(cfg, [n], grads)
-    for opts in ({}, {cm.OPT_LONG_RUN_BYTES: 0}):
+    for opts in ({}, {cm.OPT_LONG_RUN_BYTES: 1}):
         plan = lib_plan(cfg, [n], opts)
         dev = Replicas(plan, [n])
         dev.upload(grads)
@@ -395,7 +397,7 @@ def test_world_sizes_of_the_generic_kernel_including_the_maximum(W, dtype):
     elems = list(SMALL_ELEMS)
     grads = make_inputs(cfg, elems, seed=60 + W)
     ref = oracle_result(cfg, elems, grads)
-    for opts in ({}, {cm.OPT_LONG_RUN_BYTES: 0, cm.OPT_TILE_VECS: 4096}, {cm.OPT_LONG_RUN_BYTES: 1 << 40}):
+    for opts in ({}, {cm.OPT_LONG_RUN_BYTES: 1, cm.OPT_TILE_VECS: 4096}, {cm.OPT_LONG_RUN_BYTES: 1 << 40}):
         plan = lib_plan(cfg, elems, opts)
         dev = Replicas(plan, elems)
         dev.upload(grads)

@@ -38,12 +38,13 @@ def draw(rng: random.Random):
             cm.OPT_PIPELINE_MIN_BYTES: rng.choice([0, 1 << 40]),
             cm.OPT_SMALL_TILE_VECS: rng.choice([64, 256, 1024]),
             cm.OPT_SMALL_BLOCK: rng.choice([256, 512, 1024]),
-            cm.OPT_TILE_VECS: rng.choice([512, 4096]),
+            cm.OPT_TILE_VECS: rng.choice([0, 512, 4096, 8192]),
             cm.OPT_BLOCK: rng.choice([256, 1024]),
-            cm.OPT_LONG_RUN_BYTES: rng.choice([0, 1024, 32768, 32768, 1 << 40]),
+            cm.OPT_LONG_RUN_BYTES: rng.choice([0, 1, 1024, 32768, 32768, 1 << 40]),
             cm.OPT_LONG_LAUNCH_MIN_BYTES: rng.choice([0, 200000, 64 << 20]),
-            cm.OPT_STREAM_MAJOR: rng.choice([0, 2, 4]),
+            cm.OPT_STREAM_MAJOR: rng.choice([0, 2, 4, 8]),
             cm.OPT_MERGE_SMALL_BYTES: rng.choice([0, 1 << 20, 1 << 40]),
+            cm.OPT_TAIL_TILES: rng.choice([0, 3, 256]),
             cm.OPT_ALIGN_TILES: rng.choice([0, 1, 2, 3]),
             cm.OPT_LAUNCH_MIN_BYTES: rng.choice([0, 65536, 4 << 20]),
             cm.OPT_NONTEMPORAL: rng.choice([0, 1]),
