@@ -364,7 +364,7 @@ enum {
   /* The last so many long tiles of every plan stream are cut into pieces of one vector per lane
    * (16 KiB for 1024 lanes), which a workgroup fetches from all replicas at once.  When a launch
    * runs out of tiles, the workgroups still at work finish at different times; with short pieces
-   * at the end that drain is short.  Default 256 (one per compute unit); 0 switches it off.
+   * at the end that drain is short.  Default 128 (half a tile per compute unit); 0 switches it off.
    * Takes effect at the next caramel_bind. */
   CARAMEL_OPT_TAIL_TILES = 16
 };

@@ -391,7 +391,9 @@ k_ring_reduce_smt(const ReduceTile* __restrict__ tiles, const uint64_t* __restri
     const uint32_t whole = nvec / (U * B) * (U * B);  // the same for all lanes
     uint32_t v = threadIdx.x;
 #pragma unroll 1
-    for (; v < whole; v += U * B) sm_walk<W, U, 2, BF16, NT, false, true>(p, v, B, nvec, inv_w);
+    // (the walk with a guarded last row, although every row is whole here: the compiler keeps
+    // fewer values live in that form and does not spill)
+    for (; v < whole; v += U * B) sm_walk<W, U, 2, BF16, NT, true, true>(p, v, B, nvec, inv_w);
     const uint32_t rows_left = (nvec - whole + B - 1) / B;
     if (rows_left == 1) {
       if (v < nvec) {

@@ -50,7 +50,7 @@ struct TileShape {
   // The last `tail_tiles` long tiles of every stream are cut into pieces of `tail_vecs` vectors:
   // when a launch runs out of tiles the workgroups still at work finish at different times, and
   // with short pieces at the end that drain is short.
-  uint32_t tail_tiles = 256;
+  uint32_t tail_tiles = 128;
   uint32_t tail_vecs = 1024;
 };
 

@@ -129,6 +129,39 @@ def test_alignment_and_split_modes(align, mode, S):
         plan.close()
 
 
+# Segment boundaries wherever odd tensor sizes put them, for every kernel (the specialised chain
+# kernels, stream-major with 2, 4 and 8 vectors per lane and all-at-once, and the kernel for any
+# world size): tiles of every length from one vector up, whole groups of vectors, the rows left over
+# after them, ragged ends.
+BOUNDARY_SHAPES = [
+    {cm.OPT_LONG_RUN_BYTES: 1}, {cm.OPT_LONG_RUN_BYTES: 1, cm.OPT_TILE_VECS: 8192},
+    {cm.OPT_LONG_RUN_BYTES: 1, cm.OPT_STREAM_MAJOR: 4, cm.OPT_TILE_VECS: 8192},
+    {cm.OPT_LONG_RUN_BYTES: 1, cm.OPT_STREAM_MAJOR: 2, cm.OPT_TILE_VECS: 1024, cm.OPT_BLOCK: 256},
+    {cm.OPT_LONG_RUN_BYTES: 1, cm.OPT_STREAM_MAJOR: 0, cm.OPT_TILE_VECS: 2048},
+    {cm.OPT_LONG_RUN_BYTES: 1 << 40}, {cm.OPT_LONG_RUN_BYTES: 1 << 40, cm.OPT_SMALL_TILE_VECS: 1024, cm.OPT_SMALL_BLOCK: 512},
+    {cm.OPT_LONG_RUN_BYTES: 1, cm.OPT_TAIL_TILES: 0, cm.OPT_TILE_VECS: 2560},
+]
+
+
+@pytest.mark.parametrize("W", [2, 3, 4, 5, 7, 8, 12, 16, 24])
+@pytest.mark.parametrize("dtype", [oracle.F32, oracle.BF16])
+def test_segment_boundaries_at_odd_positions(W, dtype):
+    print(f"case: odd segment boundaries W={W} dtype={dtype}", flush=True)
+    # chunks only (no batching, no splitting of tensors): segment boundaries wherever the sizes put them
+    cfg = oracle.Config(W, dtype, 0, oracle.SPLIT_NONE, 1, 0, 16, 1)
+    elems = [100000, 4099, 70001, 16384, 262144 + 4, 50, 33333, 8192 * W, 1 << 20]
+    grads = make_inputs(cfg, elems, seed=900 + W)
+    ref = oracle_result(cfg, elems, grads)
+    for opts in BOUNDARY_SHAPES:
+        for phase in (0, 1280):
+            plan = lib_plan(cfg, elems, opts)
+            dev = Replicas(plan, elems, arena_phase=phase)
+            dev.upload(grads)
+            plan.allreduce()
+            assert_same_bits(dev.download(), ref, f"options {opts}, arena phase {phase}")
+            plan.close()
+
+
 @pytest.mark.parametrize("phase", [0, 256, 1280, 4096 - 256, 65536 - 512])
 @pytest.mark.parametrize("align_tiles", [0, 1, 2, 3])
 def test_tiles_cut_on_aligned_blocks_give_the_same_bits(phase, align_tiles):
