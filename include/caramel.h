@@ -286,7 +286,7 @@ int caramel_allreduce(caramel_plan* plan, void* stream);
  * a call on another stream, may still be running there - such calls race.  The plan's launch
  * options apply; timing (caramel_profile) does not cover this call.
  * EINVAL: NULL/misaligned/overlapping pointers; a plan whose tables (8 bytes per tensor and
- * worker, rounded up to 256, plus 16 bytes per tile) exceed CARAMEL_STATIC_TABLE_BYTES - nothing
+ * worker, rounded up to 256, plus 32 bytes per tile) exceed CARAMEL_STATIC_TABLE_BYTES - nothing
  * is launched then.  EHIP: a HIP call failed. */
 #define CARAMEL_STATIC_TABLE_BYTES (4u << 20)
 int caramel_allreduce_static(caramel_plan* plan, void* const* grads, void* stream);
@@ -366,7 +366,14 @@ enum {
    * runs out of tiles, the workgroups still at work finish at different times; with short pieces
    * at the end that drain is short.  Default 128 (half a tile per compute unit); 0 switches it off.
    * Takes effect at the next caramel_bind. */
-  CARAMEL_OPT_TAIL_TILES = 16
+  CARAMEL_OPT_TAIL_TILES = 16,
+  /* 1 (default): for world sizes other than 2, 4, 8 and 16 (ring order), tiles follow aligned
+   * blocks of memory across the boundaries between ring segments: a tile that contains a
+   * boundary is summed in two parts, each in its segment's order, and a run is everything of one
+   * unit that is contiguous in a tensor.  0, and always for 2, 4, 8 and 16 workers: tiles (and
+   * runs) end at segment boundaries.  Takes effect at the next caramel_bind.  Results do not
+   * depend on it. */
+  CARAMEL_OPT_SPLIT_TILES = 17
 };
 enum { CARAMEL_LAUNCH_PER_UNIT = 0, CARAMEL_LAUNCH_PER_STREAM = 1, CARAMEL_LAUNCH_AUTO = 2 };
 enum { CARAMEL_BATCH_STAGED = 0, CARAMEL_BATCH_DIRECT = 1 };

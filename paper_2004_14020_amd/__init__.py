@@ -6,7 +6,7 @@ device.py, uses PyTorch to hold device memory and streams.
 """
 from .binding import (BIN_BACKWARD, BIN_FORWARD, BATCH_DIRECT, BATCH_STAGED, BF16, F32, K_COUNT, K_PACK, K_REDUCE, K_REDUCE_SMALL, K_SEQUENCE, K_UNPACK,
                       KIND_BATCH, KIND_CHUNK, LAUNCH_AUTO, LAUNCH_PER_STREAM, LAUNCH_PER_UNIT, OPT_BATCH_PATH,
-                      PATTERN_HALVING_DOUBLING, PATTERN_RING, PATTERN_SHUFFLE, OPT_BLOCK, OPT_LAUNCH_MIN_BYTES, OPT_LAUNCH_MODE, OPT_PIPELINE_MIN_BYTES, OPT_SMALL_TILE_VECS, OPT_SMALL_BLOCK, OPT_LONG_RUN_BYTES, OPT_STREAM_MAJOR, OPT_LONG_LAUNCH_MIN_BYTES, OPT_ALIGN_TILES, OPT_MERGE_SMALL_BYTES, OPT_TAIL_TILES, OPT_MAX_GRID, OPT_NONTEMPORAL, OPT_TILE_VECS, OPT_UNROLL,
+                      PATTERN_HALVING_DOUBLING, PATTERN_RING, PATTERN_SHUFFLE, OPT_BLOCK, OPT_LAUNCH_MIN_BYTES, OPT_LAUNCH_MODE, OPT_PIPELINE_MIN_BYTES, OPT_SMALL_TILE_VECS, OPT_SMALL_BLOCK, OPT_LONG_RUN_BYTES, OPT_STREAM_MAJOR, OPT_LONG_LAUNCH_MIN_BYTES, OPT_ALIGN_TILES, OPT_MERGE_SMALL_BYTES, OPT_TAIL_TILES, OPT_SPLIT_TILES, OPT_MAX_GRID, OPT_NONTEMPORAL, OPT_TILE_VECS, OPT_UNROLL,
                       SPLIT_ADAPTIVE, SPLIT_FIXED, SPLIT_NONE, STATIC_TABLE_BYTES, CaramelError, Config, Entry, Plan, ScheduleSummary, Slot,
                       Unit, lib, net_model_fit, schedule_transfers, stream_probe, threshold_estimate,
                       PROBE_COPY, PROBE_READ, PROBE_UPDATE, PROBE_WRITE)

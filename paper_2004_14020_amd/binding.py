@@ -21,7 +21,7 @@ KIND_BATCH, KIND_CHUNK = 0, 1
 PATTERN_RING, PATTERN_HALVING_DOUBLING, PATTERN_SHUFFLE = 0, 1, 2
 (OPT_LAUNCH_MODE, OPT_BATCH_PATH, OPT_TILE_VECS, OPT_MAX_GRID, OPT_NONTEMPORAL, OPT_UNROLL, OPT_BLOCK,
  OPT_LAUNCH_MIN_BYTES, OPT_PIPELINE_MIN_BYTES, OPT_SMALL_TILE_VECS, OPT_SMALL_BLOCK, OPT_LONG_RUN_BYTES,
- OPT_STREAM_MAJOR, OPT_LONG_LAUNCH_MIN_BYTES, OPT_ALIGN_TILES, OPT_MERGE_SMALL_BYTES, OPT_TAIL_TILES) = range(17)
+ OPT_STREAM_MAJOR, OPT_LONG_LAUNCH_MIN_BYTES, OPT_ALIGN_TILES, OPT_MERGE_SMALL_BYTES, OPT_TAIL_TILES, OPT_SPLIT_TILES) = range(18)
 STATIC_TABLE_BYTES = 4 << 20
 LAUNCH_PER_UNIT, LAUNCH_PER_STREAM, LAUNCH_AUTO = 0, 1, 2
 BATCH_STAGED, BATCH_DIRECT = 0, 1

@@ -72,6 +72,7 @@ struct Options {
   uint64_t long_launch_min_bytes = 64u << 20;  // launches over long tiles likewise
   uint64_t pipeline_min_bytes = ~uint64_t(0);  // AUTO never pipelines unless told to
   uint64_t merge_small_bytes = 1u << 20;       // one launch per stream: small tiles up to this total join the long ones
+  bool split_tiles = true;                     // tiles across segment boundaries where the kernel handles them
 };
 
 // Fork/join events order work between streams of the same device; no timing, and no system-scope
@@ -688,6 +689,11 @@ int caramel_plan_set_option(caramel_plan* p, uint32_t option, uint64_t value) {
       p->opt.shape.tail_tiles = uint32_t(value);
       p->fixed_valid = false;
       return CARAMEL_OK;
+    case CARAMEL_OPT_SPLIT_TILES:
+      if (value > 1) return fail(CARAMEL_EINVAL, "split_tiles must be 0 or 1");
+      p->opt.split_tiles = value != 0;
+      p->fixed_valid = false;
+      return CARAMEL_OK;
     case CARAMEL_OPT_MERGE_SMALL_BYTES:
       p->opt.merge_small_bytes = value;
       regroup();
@@ -752,6 +758,10 @@ void fill_binding(const caramel_plan* p, std::vector<uint64_t>&& rows, Binding& 
   //    else 64 KiB.
   bd.shape.tail_vecs = p->opt.block;  // one vector per lane: a piece is fetched from all replicas at once
   const caramel_config& c = p->host.cfg;
+  //  * tiles may straddle a segment boundary where the kernel for the world size sums the two
+  //    parts in their own orders (the kernel for any world size; W = 48, 4 MiB chunks: 63 -> 7x %
+  //    of peak); the kernels specialised for 2, 4, 8 and 16 workers get tiles inside one segment.
+  bd.shape.split_tiles = p->opt.split_tiles && reduce_handles_split_tiles(c.world);
   uint64_t replica_bytes = 0;
   for (uint64_t e : p->host.tensor_elems) replica_bytes += e * p->host.elem_size();
   if (bd.shape.long_run_bytes == 0) bd.shape.long_run_bytes = replica_bytes < (32u << 20) ? ~uint64_t(0) : 16u << 10;

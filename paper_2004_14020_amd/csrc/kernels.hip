@@ -81,6 +81,19 @@ struct Chain {
     a = a + o.a;
     if constexpr (BF16) b = b + o.b;
   }
+  // becomes `o` in the lanes where `c` holds (a select on the bits: no arithmetic)
+  __device__ __forceinline__ void take_if(bool c, const Chain& o) {
+    a.x = c ? o.a.x : a.x;
+    a.y = c ? o.a.y : a.y;
+    a.z = c ? o.a.z : a.z;
+    a.w = c ? o.a.w : a.w;
+    if constexpr (BF16) {
+      b.x = c ? o.b.x : b.x;
+      b.y = c ? o.b.y : b.y;
+      b.z = c ? o.b.z : b.z;
+      b.w = c ? o.b.w : b.w;
+    }
+  }
   __device__ __forceinline__ u32x4 finish(float inv_w) {
     if constexpr (BF16) {
       const f32x4 ya = a * inv_w, yb = b * inv_w;
@@ -447,31 +460,64 @@ k_ring_reduce_any(const ReduceTile* __restrict__ tiles, const uint64_t* __restri
     const uint64_t* row = rows + size_t(tl.row) * W;
     const uint32_t nvec = tl.n_elems / VE;
     const uint32_t B = blockDim.x;
-    // one pass of the chain over N vectors of this lane, B apart, starting at v
-    auto chain = [&](uint32_t v, auto n_tag, auto ragged_tag) {
+    const uint32_t late_from = tl.split / VE;  // used for split tiles only
+    // One pass of the chain over N vectors of this lane, B apart, starting at v.
+    // SPLIT (a tile across a segment boundary, W >= 2): the workers are visited in the tile's
+    // order and then the first one once more, W + 1 steps; the lanes before the boundary add the
+    // values of steps 0 .. W-1, the late lanes (whose sums start one worker later) those of steps
+    // 1 .. W.  A lane asks for no data in the step it sits out, so nothing is fetched twice and
+    // the whole workgroup still reads one replica at a time.
+    auto chain = [&](uint32_t v, auto n_tag, auto ragged_tag, auto split_tag) {
       constexpr int N = decltype(n_tag)::value;
       constexpr bool RAGGED = decltype(ragged_tag)::value;
+      constexpr bool SPLIT = decltype(split_tag)::value;
       Chain<BF16> acc[N];
       u32x4 cur[N], nxt[N];
       const bool last_ok = !RAGGED || v + (N - 1) * B < nvec;
       uint32_t off[N];
+      bool late[N];
 #pragma unroll
-      for (int u = 0; u < N; ++u) off[u] = (v + u * B) * 16u;
+      for (int u = 0; u < N; ++u) {
+        off[u] = (v + u * B) * 16u;
+        late[u] = SPLIT && v + u * B >= late_from;
+      }
       if (RAGGED && !last_ok) off[N - 1] = (nvec - 1) * 16u;
       uint32_t w = tl.first;
       gvec_ptr base = reinterpret_cast<gvec_ptr>(row[w]) + tl.vec_off;
 #pragma unroll
-      for (int u = 0; u < N; ++u) cur[u] = ld<NT>(at(base, off[u]));
-      for (uint32_t k = 1; k < W; ++k) {
+      for (int u = 0; u < N; ++u) {
+        cur[u] = u32x4{0u, 0u, 0u, 0u};
+        if (!late[u]) cur[u] = ld<NT>(at(base, off[u]));
+      }
+      const uint32_t steps = SPLIT ? W + 1 : W;
+      for (uint32_t k = 1; k < steps; ++k) {
         w = (w + 1 == W) ? 0 : w + 1;
         base = reinterpret_cast<gvec_ptr>(row[w]) + tl.vec_off;
+        if (SPLIT && k == W) {
+          // back at the first worker: only the late lanes still need its value
 #pragma unroll
-        for (int u = 0; u < N; ++u) nxt[u] = ld<NT>(at(base, off[u]));
+          for (int u = 0; u < N; ++u) {
+            nxt[u] = cur[u];
+            if (late[u]) nxt[u] = ld<NT>(at(base, off[u]));
+          }
+        } else {
+#pragma unroll
+          for (int u = 0; u < N; ++u) nxt[u] = ld<NT>(at(base, off[u]));
+        }
         __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
         for (int u = 0; u < N; ++u) {
-          if (k == 1) acc[u].start(cur[u]);
-          else acc[u].add(cur[u]);
+          // cur holds the values of step k - 1
+          if (k == 1) {
+            acc[u].start(cur[u]);  // (a late lane starts over at the next step)
+          } else if (SPLIT && k == 2) {
+            Chain<BF16> fresh;
+            fresh.start(cur[u]);
+            acc[u].add(cur[u]);
+            acc[u].take_if(late[u], fresh);
+          } else {
+            acc[u].add(cur[u]);
+          }
           cur[u] = nxt[u];
         }
         __builtin_amdgcn_sched_barrier(0);
@@ -479,8 +525,14 @@ k_ring_reduce_any(const ReduceTile* __restrict__ tiles, const uint64_t* __restri
       u32x4 y[N];
 #pragma unroll
       for (int u = 0; u < N; ++u) {
-        if (W == 1) acc[u].start(cur[u]);
-        else acc[u].add(cur[u]);
+        if constexpr (SPLIT) {
+          Chain<BF16> more = acc[u];
+          more.add(cur[u]);
+          acc[u].take_if(late[u], more);
+        } else {
+          if (W == 1) acc[u].start(cur[u]);
+          else acc[u].add(cur[u]);
+        }
         y[u] = acc[u].finish(inv_w);
       }
       for (uint32_t k = 0; k < W; ++k) {
@@ -492,39 +544,49 @@ k_ring_reduce_any(const ReduceTile* __restrict__ tiles, const uint64_t* __restri
     };
     const uint32_t whole = nvec / (U * B) * (U * B);  // the same for all lanes
     uint32_t v = threadIdx.x;
-    for (; v < whole; v += U * B) chain(v, std::integral_constant<int, U>{}, std::false_type{});
     const uint32_t rows_left = (nvec - whole + B - 1) / B;
-    static_assert(U == 4, "the dispatch below lists the row counts of U = 4");
-    if (rows_left == 1 && v < nvec) {
-      // at most one vector per lane: nothing to walk; fetch the workers' values eight at a time
-      Chain<BF16> acc;
-      for (uint32_t k0 = 0; k0 < W; k0 += 8) {
-        u32x4 x[8];
+    static_assert(U == 4, "the dispatches below list the row counts of U = 4");
+    if (tl.split) {
+      for (; v < whole; v += U * B) chain(v, std::integral_constant<int, U>{}, std::false_type{}, std::true_type{});
+      if (rows_left == 1) chain(v, std::integral_constant<int, 1>{}, std::true_type{}, std::true_type{});
+      if (rows_left == 2) chain(v, std::integral_constant<int, 2>{}, std::true_type{}, std::true_type{});
+      if (rows_left == 3) chain(v, std::integral_constant<int, 3>{}, std::true_type{}, std::true_type{});
+      if (rows_left == 4) chain(v, std::integral_constant<int, 4>{}, std::true_type{}, std::true_type{});
+    } else {
+      for (; v < whole; v += U * B) chain(v, std::integral_constant<int, U>{}, std::false_type{}, std::false_type{});
+      if (rows_left == 1 && v < nvec) {
+        // at most one vector per lane: nothing to walk; fetch the workers' values eight at a time
+        Chain<BF16> acc;
+        for (uint32_t k0 = 0; k0 < W; k0 += 8) {
+          u32x4 x[8];
 #pragma unroll
-        for (uint32_t i = 0; i < 8; ++i)
-          if (k0 + i < W) {
-            uint32_t w = tl.first + k0 + i;
-            if (w >= W) w -= W;
-            x[i] = ld<NT>(at(reinterpret_cast<gvec_ptr>(row[w]) + tl.vec_off, v * 16u));
-          }
-        __builtin_amdgcn_sched_barrier(0);
+          for (uint32_t i = 0; i < 8; ++i)
+            if (k0 + i < W) {
+              uint32_t w = tl.first + k0 + i;
+              if (w >= W) w -= W;
+              x[i] = ld<NT>(at(reinterpret_cast<gvec_ptr>(row[w]) + tl.vec_off, v * 16u));
+            }
+          __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
-        for (uint32_t i = 0; i < 8; ++i)
-          if (k0 + i < W) {
-            if (k0 + i == 0) acc.start(x[i]);
-            else acc.add(x[i]);
-          }
+          for (uint32_t i = 0; i < 8; ++i)
+            if (k0 + i < W) {
+              if (k0 + i == 0) acc.start(x[i]);
+              else acc.add(x[i]);
+            }
+        }
+        const u32x4 y = acc.finish(inv_w);
+        for (uint32_t k = 0; k < W; ++k) st<NT>(at(reinterpret_cast<gvec_ptr>(row[k]) + tl.vec_off, v * 16u), y);
       }
-      const u32x4 y = acc.finish(inv_w);
-      for (uint32_t k = 0; k < W; ++k) st<NT>(at(reinterpret_cast<gvec_ptr>(row[k]) + tl.vec_off, v * 16u), y);
+      if (rows_left == 2) chain(v, std::integral_constant<int, 2>{}, std::true_type{}, std::false_type{});
+      if (rows_left == 3) chain(v, std::integral_constant<int, 3>{}, std::true_type{}, std::false_type{});
+      if (rows_left == 4) chain(v, std::integral_constant<int, 4>{}, std::true_type{}, std::false_type{});
     }
-    if (rows_left == 2) chain(v, std::integral_constant<int, 2>{}, std::true_type{});
-    if (rows_left == 3) chain(v, std::integral_constant<int, 3>{}, std::true_type{});
-    if (rows_left == 4) chain(v, std::integral_constant<int, 4>{}, std::true_type{});
     const uint32_t rem = tl.n_elems - nvec * VE;
     if (threadIdx.x < rem) {
       const size_t e = size_t(tl.vec_off) * VE + nvec * VE + threadIdx.x;
-      uint32_t w = tl.first;
+      // an element behind the boundary of a split tile starts one worker later
+      uint32_t w = tl.first + ((tl.split && nvec * VE + threadIdx.x >= tl.split) ? 1u : 0u);
+      if (w >= W) w -= W;
       if constexpr (BF16) {
         float acc = widen(reinterpret_cast<gu16_ptr>(row[w])[e]);
         for (uint32_t k = 1; k < W; ++k) {
@@ -772,6 +834,11 @@ hipError_t launch_ring_reduce(const ReduceArgs& a, hipStream_t s) {
   }
 #undef CARAMEL_ANY
   return hipGetLastError();
+}
+
+// the kernel for any world size does; the ones specialised for 2, 4, 8 and 16 workers do not
+bool reduce_handles_split_tiles(uint32_t world) {
+  return world != 2 && world != 4 && world != 8 && world != 16;
 }
 
 hipError_t launch_copy(const CopyArgs& a, hipStream_t s) {

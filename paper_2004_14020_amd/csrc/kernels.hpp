@@ -35,6 +35,9 @@ struct CopyArgs {
 
 // Ring reduce-scatter arithmetic + 1/W scaling + all-gather for a range of tiles.
 hipError_t launch_ring_reduce(const ReduceArgs& a, hipStream_t stream);
+// Whether the kernel that launch_ring_reduce picks for this world size handles tiles that straddle
+// a segment boundary (ReduceTile::split != 0).  The tile tables must hold none otherwise.
+bool reduce_handles_split_tiles(uint32_t world);
 // Segmented gather (pack) or scatter (unpack) driven by the copy-tile table.
 hipError_t launch_copy(const CopyArgs& a, hipStream_t stream);
 

@@ -10,13 +10,18 @@
 
 namespace caramel {
 
-// One workgroup's share of the ring reduction: a run of elements that lies inside ONE ring
-// segment, so the chain of workers is the same for every lane.
+// One workgroup's share of the ring reduction: a piece of one row that lies inside one ring
+// segment, or straddles the boundary between two consecutive ones.  Inside a segment the chain of
+// workers is the same for every lane; the sums of the next segment start one worker later.
 struct ReduceTile {
   uint32_t row;      // pointer row
   uint32_t first;    // worker whose value is read first: (segment + 1) mod W for the ring, else 0
-  uint32_t vec_off;  // offset of the run inside the row, in 16-byte vectors
-  uint32_t n_elems;  // elements in the run; only a run that ends a tensor may be ragged
+  uint32_t vec_off;  // offset of the piece inside the row, in 16-byte vectors
+  uint32_t n_elems;  // elements in the piece; only a piece that ends a tensor may be ragged
+  uint32_t split;    // 0, or the number of elements that belong to the first of two segments (a
+                     // multiple of the vector size): the sums of the elements from `split` on
+                     // start at worker first + 1 (mod W)
+  uint32_t pad_[3];
 };
 
 // One wavefront's share of pack / unpack: a run of one batch member.
@@ -33,11 +38,14 @@ struct Range {
   uint32_t begin = 0, count = 0;
 };
 
-// A run is a maximal piece of one tensor (or of the fused buffer) inside one ring segment of
-// one unit: a chunk unit has one run per segment, a batch unit addressed through its members
-// one per member and segment.  Long runs are cut into long tiles, for 1024-lane workgroups that
-// walk the replicas one after the other; the rest into small tiles, for 256-lane workgroups
-// that fetch all replicas at once.
+// A run is a maximal contiguous piece of one row (a tensor, or the fused buffer) that belongs to
+// one unit: a whole chunk, a whole member of a batch unit reduced in place, or a batch unit's
+// region of the fused buffer.  It consists of one part per ring segment it crosses.  Runs are
+// cut into tiles along aligned blocks of memory, whatever the segment boundaries; a tile that
+// contains a boundary carries its position (`split`), and where a tile would contain two, it
+// ends at the second.  Long runs are cut into long tiles, for 1024-lane workgroups that walk the
+// replicas one after the other; the rest into small tiles, for 256-lane workgroups that fetch
+// all replicas at once.
 struct TileShape {
   uint32_t long_vecs = 0;              // vectors per long tile; 0 (options only) = chosen at bind: 4096 or 8192
   uint32_t small_vecs = 256;           // vectors per small tile
@@ -47,6 +55,7 @@ struct TileShape {
   // the run is shortened so that all later ones start on multiples of the tile size in memory
   // (bit 0: small tiles, bit 1: long tiles).
   uint32_t align_tiles = 3;
+  bool split_tiles = false;  // tiles may straddle a segment boundary (set at bind if the kernel handles them)
   // The last `tail_tiles` long tiles of every stream are cut into pieces of `tail_vecs` vectors:
   // when a launch runs out of tiles the workgroups still at work finish at different times, and
   // with short pieces at the end that drain is short.

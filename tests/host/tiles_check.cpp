@@ -1,7 +1,8 @@
 // Host-only check of the planner and the tile tables, built with AddressSanitizer and UBSan.
 // For random configurations it verifies what the kernels rely on: every tile stays inside
 // its row, starts on a 16-byte vector, lies inside one ring segment with the right first
-// worker, and the tiles of a table cover every element exactly once.
+// worker -- or straddles one boundary between two segments whose chains start one worker apart,
+// at the position the tile names --, and the tiles of a table cover every element exactly once.
 #include <algorithm>
 #include <cstdint>
 #include <cstdio>
@@ -42,6 +43,7 @@ static void check_case(const caramel_config& cfg, const std::vector<uint64_t>& e
   shape.align_tiles = uint32_t(addr_seed >> 8) & 3u;
   shape.tail_tiles = (addr_seed >> 10) & 1 ? 0 : uint32_t(1 + (addr_seed >> 11) % 40);
   shape.tail_vecs = (addr_seed >> 17) & 1 ? 64 : 16;
+  shape.split_tiles = ((addr_seed >> 18) & 1) != 0;
   // addr_seed 0: no addresses (tiles start where runs start).  Otherwise made-up base addresses,
   // aligned as bind demands; odd seeds give every replica the same position inside a tile-sized
   // block (tiles must then start on multiples of the tile size), even seeds different ones.
@@ -76,18 +78,21 @@ static void check_case(const caramel_config& cfg, const std::vector<uint64_t>& e
         const uint64_t cap = uint64_t(cls == kLong ? tile_vecs : small_vecs);
         CHECK(uint64_t(r.begin) + r.count <= tiles.size());
         total_tiles += r.count;
-        uint32_t prev_row = ~0u, prev_seg = ~0u;
+        uint32_t prev_row = ~0u, prev_last_first = ~0u;
         uint64_t prev_end = ~0ull;
-        // length of the run (same row, same segment, contiguous) a tile belongs to
+        // first worker of a tile's last element
+        auto last_first = [&](const ReduceTile& t) { return t.split ? (t.first + 1) % uint32_t(W) : t.first; };
+        // consecutive tiles of one run: adjacent in the same row and, where tiles end at segment
+        // boundaries, of the same segment (a ring run's first worker identifies its segment; the
+        // other patterns have first == 0 everywhere and their segments form one run)
+        auto same_run = [&](const ReduceTile& a, const ReduceTile& b) {
+          return a.row == b.row && uint64_t(a.vec_off) * ve + a.n_elems == uint64_t(b.vec_off) * ve &&
+                 (shape.split_tiles || last_first(a) == b.first);
+        };
         auto run_len = [&](uint32_t i) {
-          auto seg_of = [&](const ReduceTile& t) { return t.first; };
           uint32_t lo = i, hi = i;
-          while (lo > r.begin && tiles[lo - 1].row == tiles[lo].row && seg_of(tiles[lo - 1]) == seg_of(tiles[lo]) &&
-                 uint64_t(tiles[lo - 1].vec_off) * ve + tiles[lo - 1].n_elems == uint64_t(tiles[lo].vec_off) * ve)
-            --lo;
-          while (hi + 1 < r.begin + r.count && tiles[hi + 1].row == tiles[hi].row && seg_of(tiles[hi + 1]) == seg_of(tiles[hi]) &&
-                 uint64_t(tiles[hi].vec_off) * ve + tiles[hi].n_elems == uint64_t(tiles[hi + 1].vec_off) * ve)
-            ++hi;
+          while (lo > r.begin && same_run(tiles[lo - 1], tiles[lo])) --lo;
+          while (hi + 1 < r.begin + r.count && same_run(tiles[hi], tiles[hi + 1])) ++hi;
           uint64_t n = 0;
           for (uint32_t k = lo; k <= hi; ++k) n += tiles[k].n_elems;
           return n;
@@ -124,26 +129,40 @@ static void check_case(const caramel_config& cfg, const std::vector<uint64_t>& e
             }
             CHECK(found);
           }
+          // every element's segment -> the worker its sum starts at
+          CHECK(t.split % ve == 0 && t.split < t.n_elems);
+          if (!shape.split_tiles) CHECK(t.split == 0);
           uint32_t c = 0;
-          while (c + 1 < W && seg[c + 1] <= unit_pos) ++c;
-          CHECK(unit_pos >= seg[c] && unit_pos + t.n_elems <= seg[c + 1]);
-          CHECK(t.first == (cfg.pattern == CARAMEL_PATTERN_RING ? (c + 1) % W : 0));
-          // the class follows the length of the run (a ring run's first worker identifies its
-          // segment; the other patterns have first == 0 everywhere, so neighbours may merge:
-          // there only the lower bound of a long run can be checked)
+          for (uint64_t k = 0; k < t.n_elems; ++k) {
+            while (c + 1 < W && seg[c + 1] <= unit_pos + k) ++c;
+            CHECK(unit_pos + k >= seg[c] && unit_pos + k < seg[c + 1]);
+            const uint32_t want = cfg.pattern == CARAMEL_PATTERN_RING ? uint32_t((c + 1) % W) : 0u;
+            const uint32_t have = (t.split && k >= t.split) ? uint32_t((t.first + 1) % W) : t.first;
+            if (have != want) {
+              CHECK(have == want);
+              break;
+            }
+          }
+          // a boundary the tile names is a real one
+          if (t.split) CHECK(cfg.pattern == CARAMEL_PATTERN_RING && W > 1);
+          // the class follows the length of the run
           const uint64_t rl = run_len(i) * es;
           if (cls == kLong) CHECK(rl >= long_run_bytes);
-          else if (cfg.pattern == CARAMEL_PATTERN_RING && W > 1) CHECK(rl < long_run_bytes);
+          else CHECK(rl < long_run_bytes);
           if ((addr_seed & 1) && (shape.align_tiles & (cls == kLong ? 2u : 1u))) {
-            // same phase in every replica: a tile that does not begin its run begins an aligned block
-            const bool continues = i > r.begin && prev_row == t.row && prev_end == e0 && prev_seg == c;
+            // same phase in every replica: a tile that does not begin its run begins an aligned
+            // block, unless the tile before it had to end at a segment boundary (a tile holds at
+            // most one)
+            const bool at_boundary = std::find(seg, seg + W + 1, unit_pos) != seg + W + 1;
+            const bool continues = i > r.begin && prev_row == t.row && prev_end == e0 && !at_boundary &&
+                                   (shape.split_tiles || prev_last_first == t.first);
             // (pieces of the tiles cut up at the end of a stream start on multiples of the piece size)
             const uint64_t block = cls == kLong && shape.tail_tiles ? std::min<uint64_t>(cap, shape.tail_vecs) : cap;
             if (continues) CHECK((addr[size_t(t.row) * W] + e0 * es) % (block * 16) == 0);
           }
           prev_row = t.row;
           prev_end = e1;
-          prev_seg = c;
+          prev_last_first = last_first(t);
           std::vector<uint8_t>& s = seen[t.row];
           if (s.empty()) s.assign(row_elems(t.row), 0);
           for (uint64_t e = e0; e < e1; ++e) {

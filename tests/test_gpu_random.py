@@ -46,6 +46,7 @@ def draw(rng: random.Random):
             cm.OPT_MERGE_SMALL_BYTES: rng.choice([0, 1 << 20, 1 << 40]),
             cm.OPT_TAIL_TILES: rng.choice([0, 3, 256]),
             cm.OPT_ALIGN_TILES: rng.choice([0, 1, 2, 3]),
+            cm.OPT_SPLIT_TILES: rng.choice([0, 1, 1]),
             cm.OPT_LAUNCH_MIN_BYTES: rng.choice([0, 65536, 4 << 20]),
             cm.OPT_NONTEMPORAL: rng.choice([0, 1]),
             cm.OPT_UNROLL: rng.choice([0, 1, 2, 4]),
