@@ -26,6 +26,10 @@
  * must keep them alive until the stream work has completed.  The library
  * allocates only its own small descriptor tables (at caramel_bind).
  *
+ * Tracing.  With CARAMEL_TRACE=1 in the environment (read once per process) the library writes
+ * one line to stderr per unit at caramel_bind (kind, plan stream, bytes, tiles) and one per
+ * kernel launch (call number, stream, tile range, workgroup shape, bytes per replica).
+ *
  * Errors.  Every function returns a status; nothing throws across the ABI.  On
  * a non-zero status nothing has been launched unless stated, and
  * caramel_last_error() describes the failure.

@@ -6,6 +6,7 @@
 #include <cmath>
 #include <cstdarg>
 #include <cstdio>
+#include <cstdlib>
 #include <cstring>
 #include <memory>
 #include <mutex>
@@ -86,6 +87,16 @@ struct LaunchGroup {
   Range reduce;
   uint64_t elems;  // elements per replica the launch covers
 };
+
+// CARAMEL_TRACE=1 in the environment: one line on stderr per bound unit and per kernel launch
+// (what is launched where, over which tiles).  Read once.
+bool tracing() {
+  static const bool on = [] {
+    const char* v = std::getenv("CARAMEL_TRACE");
+    return v && *v && std::strcmp(v, "0") != 0;
+  }();
+  return on;
+}
 
 struct TimedLaunch {
   int kind;
@@ -245,6 +256,13 @@ int run_reduce(caramel_plan* p, const Binding& bd, const DeviceTables& dt, bool 
     a.stream_major = std::min(p->opt.stream_major, rows >= 8 ? 8u : (rows >= 4 ? 4u : 2u));
   }
   a.max_grid = p->opt.max_grid;
+  if (tracing())
+    std::fprintf(stderr,
+                 "caramel: call %llu reduce  stream %p (plan stream %u, from unit %u) %s tiles [%u, %u) %s, %u lanes, "
+                 "%u vectors per lane and worker, %llu bytes per replica\n",
+                 (unsigned long long)p->call_no, (void*)s, g.lane, g.first_unit, lng ? "long" : "small", r.begin,
+                 r.begin + r.count, direct ? "in place" : "staged", a.block, a.stream_major ? a.stream_major : a.unroll,
+                 (unsigned long long)(g.elems * p->host.elem_size()));
   if (!timed) {
     HIP_TRY(launch_ring_reduce(a, s));
     return CARAMEL_OK;
@@ -265,6 +283,9 @@ int run_copy(caramel_plan* p, const DeviceTables& dt, bool unpack, Range r, hipS
   a.fused_row = uint32_t(p->host.tensor_elems.size());
   a.bf16 = p->host.cfg.dtype == CARAMEL_BF16;
   a.unpack = unpack;
+  if (tracing())
+    std::fprintf(stderr, "caramel: call %llu %s stream %p copy tiles [%u, %u)\n", (unsigned long long)p->call_no,
+                 unpack ? "unpack " : "pack   ", (void*)s, r.begin, r.begin + r.count);
   Timed timer(p, unpack ? CARAMEL_K_UNPACK : CARAMEL_K_PACK, s);
   HIP_TRY(launch_copy(a, s));
   return CARAMEL_OK;
@@ -815,6 +836,17 @@ int bind_plan(caramel_plan* p, void* const* grads, void* fused_ws) {
   }
   p->has_ws = fused_ws != nullptr;
   p->bound = true;
+  if (tracing()) {
+    std::fprintf(stderr, "caramel: bind  %zu units, long tiles of %u vectors, small of %u, runs of %llu bytes or more are long\n",
+                 h.units.size(), p->bind.shape.long_vecs, p->bind.shape.small_vecs,
+                 (unsigned long long)p->bind.shape.long_run_bytes);
+    for (size_t u = 0; u < h.units.size(); ++u) {
+      const UnitTiles& ut = p->bind.tt.direct_unit[u];
+      std::fprintf(stderr, "caramel: unit %zu %s stream %u %llu bytes per replica: %u long + %u small tiles\n", u,
+                   h.units[u].kind == CARAMEL_KIND_BATCH ? "batch" : "chunk", h.units[u].stream,
+                   (unsigned long long)(h.units[u].elems * h.elem_size()), ut.tiles[kLong].count, ut.tiles[kSmall].count);
+    }
+  }
   return CARAMEL_OK;
 }
 }  // namespace

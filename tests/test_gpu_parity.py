@@ -510,3 +510,30 @@ def test_timing_aware_plan_runs_bit_exact():
     plan.allreduce()
     assert_same_bits(dev.download(), ref, "timed plan")
     plan.close()
+
+
+def test_trace_log_names_every_launch():
+    """CARAMEL_TRACE=1 is read once per process, so the traced call runs in a child process."""
+    import os
+    import subprocess
+    import sys
+    print("case: CARAMEL_TRACE host log", flush=True)
+    code = (
+        "import torch, paper_2004_14020_amd as cm\n"
+        "elems = [300000, 100, 5000]\n"
+        "plan = cm.Plan(4, elems, batch_threshold_bytes=65536, split_mode=cm.SPLIT_FIXED, split_bytes=1 << 19, num_streams=2)\n"
+        "g = [[torch.ones(n, device='cuda:0') for n in elems] for _ in range(4)]\n"
+        "plan.bind([[t.data_ptr() for t in r] for r in g], None)\n"
+        "plan.allreduce(torch.cuda.current_stream().cuda_stream)\n"
+        "torch.cuda.synchronize()\n"
+        "assert all(float(t.min()) == 1.0 and float(t.max()) == 1.0 for r in g for t in r)\n"
+    )
+    root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+    env = dict(os.environ, CARAMEL_TRACE="1", PYTHONPATH=root)
+    res = subprocess.run([sys.executable, "-c", code], env=env, capture_output=True, text=True, timeout=240)
+    assert res.returncode == 0, res.stderr[-2000:]
+    lines = [l for l in res.stderr.splitlines() if l.startswith("caramel:")]
+    units = [l for l in lines if l.startswith("caramel: unit ")]
+    launches = [l for l in lines if " reduce " in l]
+    assert len(units) == 4 and any("batch" in l for l in units) and sum("chunk" in l for l in units) == 3, lines
+    assert launches and all("call 1 " in l for l in launches), lines
