@@ -780,7 +780,7 @@ void fill_binding(const caramel_plan* p, std::vector<uint64_t>&& rows, Binding& 
   bd.shape.tail_vecs = p->opt.block;  // one vector per lane: a piece is fetched from all replicas at once
   const caramel_config& c = p->host.cfg;
   //  * tiles may straddle a segment boundary where the kernel for the world size sums the two
-  //    parts in their own orders (the kernel for any world size; W = 48, 4 MiB chunks: 63 -> 7x %
+  //    parts in their own orders (the kernel for any world size; W = 48, 4 MiB chunks: 63 -> 71 %
   //    of peak); the kernels specialised for 2, 4, 8 and 16 workers get tiles inside one segment.
   bd.shape.split_tiles = p->opt.split_tiles && reduce_handles_split_tiles(c.world);
   uint64_t replica_bytes = 0;
