@@ -140,6 +140,9 @@ BOUNDARY_SHAPES = [
     {cm.OPT_LONG_RUN_BYTES: 1, cm.OPT_STREAM_MAJOR: 0, cm.OPT_TILE_VECS: 2048},
     {cm.OPT_LONG_RUN_BYTES: 1 << 40}, {cm.OPT_LONG_RUN_BYTES: 1 << 40, cm.OPT_SMALL_TILE_VECS: 1024, cm.OPT_SMALL_BLOCK: 512},
     {cm.OPT_LONG_RUN_BYTES: 1, cm.OPT_TAIL_TILES: 0, cm.OPT_TILE_VECS: 2560},
+    # no pieces at the end of a stream: whole 64 KiB and 128 KiB tiles, i.e. whole groups of vectors per lane
+    {cm.OPT_LONG_RUN_BYTES: 1, cm.OPT_TAIL_TILES: 0}, {cm.OPT_LONG_RUN_BYTES: 1, cm.OPT_TAIL_TILES: 0, cm.OPT_TILE_VECS: 8192},
+    {cm.OPT_LONG_RUN_BYTES: 1, cm.OPT_TAIL_TILES: 2, cm.OPT_TILE_VECS: 16384},
 ]
 
 
