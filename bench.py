@@ -239,6 +239,29 @@ def main() -> int:
     c_loop = {"host_us_per_call": round(host_us, 2), "stream_us_per_call": round(stream_us, 2),
               "GB/s_on_stream": round(alg_bytes / stream_us / 1e3, 1)}
 
+    # staged route only: the pack and unpack kernels (k_copy) timed on their own; each moves the
+    # batched parameters of every replica once: 2 * s bytes per small element and replica
+    copy = None
+    if args.batch_path == "staged":
+        units = plan.units()
+        small = sum(e.elems for e in plan.entries() if units[e.unit].kind == cm.KIND_BATCH)
+        moved = 2 * small * es * wl.world
+        copy = {"kernel": "k_copy", "bytes_per_call": moved}
+        for label, fn in (("pack", plan.pack), ("unpack", plan.unpack)):
+            best = None
+            for _ in range(3):
+                for _ in range(3):
+                    fn(stream)
+                torch.cuda.synchronize()
+                c0 = time.perf_counter()
+                for _ in range(30):
+                    fn(stream)
+                torch.cuda.synchronize()
+                dt = (time.perf_counter() - c0) / 30
+                best = dt if best is None else min(best, dt)
+            copy[label] = {"ms": round(best * 1e3, 5), "GB/s": round(moved / best / 1e9, 1),
+                           "frac": round(moved / best / 1e9 / HBM_PEAK_GBS, 4)}
+
     cpu = None
     if not args.no_cpu_baseline:
         import oracle
@@ -297,6 +320,7 @@ def main() -> int:
                    "pattern": args.pattern, "launch_mode": args.launch_mode or "auto", "batch_path": args.batch_path or "direct"},
         "roofline": roofline,
         "calls_issued_from_c": c_loop,
+        "pack_unpack": copy,
         "cpu_baseline": cpu,
     }
     print(json.dumps(out))

@@ -324,7 +324,8 @@ enum {
   CARAMEL_OPT_TILE_VECS = 2,
   /* Upper bound on workgroups per reduce launch (0 = one workgroup per tile). */
   CARAMEL_OPT_MAX_GRID = 3,
-  /* Non-zero: streaming (non-temporal) loads/stores in the reduce kernel. */
+  /* Non-zero (default): streaming (non-temporal) loads/stores in the reduce kernels, and in pack /
+   * unpack when the fused buffers of all workers together hold 256 MiB or more. */
   CARAMEL_OPT_NONTEMPORAL = 4,
   /* 16-byte vectors each lane keeps in flight per worker where all replicas are fetched at
    * once: 1, 2 or 4; 0 = chosen from W. */

@@ -697,7 +697,7 @@ k_ring_reduce_tree_any(const ReduceTile* __restrict__ tiles, const uint64_t* __r
 
 // ------------------------------------------------------------------------------------------
 // pack / unpack: one wavefront per copy tile, grid.y = worker.
-template <typename E, bool UNPACK>
+template <typename E, bool UNPACK, bool NT>
 __global__ void __launch_bounds__(kBlock)
 k_copy(const CopyTile* __restrict__ tiles, const uint64_t* __restrict__ rows, uint32_t begin, uint32_t count,
        uint32_t W, uint32_t fused_row) {
@@ -714,13 +714,13 @@ k_copy(const CopyTile* __restrict__ tiles, const uint64_t* __restrict__ rows, ui
   gvec_ptr dst = UNPACK ? tp : fp;
   uint32_t v = lane;
   for (; v + 3 * 64 < nvec; v += 4 * 64) {
-    const u32x4 a = src[v], b = src[v + 64], c = src[v + 128], d = src[v + 192];
-    dst[v] = a;
-    dst[v + 64] = b;
-    dst[v + 128] = c;
-    dst[v + 192] = d;
+    const u32x4 a = ld<NT>(src + v), b = ld<NT>(src + v + 64), c = ld<NT>(src + v + 128), d = ld<NT>(src + v + 192);
+    st<NT>(dst + v, a);
+    st<NT>(dst + v + 64, b);
+    st<NT>(dst + v + 128, c);
+    st<NT>(dst + v + 192, d);
   }
-  for (; v < nvec; v += 64) dst[v] = src[v];
+  for (; v < nvec; v += 64) st<NT>(dst + v, ld<NT>(src + v));
   // ragged end of a member, and (pack only) the +0.0 padding up to the next member
   CARAMEL_GLOBAL E* se = reinterpret_cast<CARAMEL_GLOBAL E*>(src);
   CARAMEL_GLOBAL E* de = reinterpret_cast<CARAMEL_GLOBAL E*>(dst);
@@ -845,7 +845,12 @@ hipError_t launch_copy(const CopyArgs& a, hipStream_t s) {
   if (a.count == 0) return hipSuccess;
   const dim3 grid((a.count + kBlock / 64 - 1) / (kBlock / 64), a.world);
 #define CARAMEL_CP(E, UN) \
-  hipLaunchKernelGGL((k_copy<E, UN>), grid, dim3(kBlock), 0, s, a.tiles, a.rows, a.begin, a.count, a.world, a.fused_row)
+  do { \
+    if (a.nontemporal) \
+      hipLaunchKernelGGL((k_copy<E, UN, true>), grid, dim3(kBlock), 0, s, a.tiles, a.rows, a.begin, a.count, a.world, a.fused_row); \
+    else \
+      hipLaunchKernelGGL((k_copy<E, UN, false>), grid, dim3(kBlock), 0, s, a.tiles, a.rows, a.begin, a.count, a.world, a.fused_row); \
+  } while (0)
   if (a.bf16) {
     if (a.unpack) CARAMEL_CP(uint16_t, true); else CARAMEL_CP(uint16_t, false);
   } else {

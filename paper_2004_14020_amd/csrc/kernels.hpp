@@ -31,6 +31,7 @@ struct CopyArgs {
   uint32_t fused_row;
   bool bf16;
   bool unpack;  // false: tensors -> fused buffers; true: fused buffers -> tensors
+  bool nontemporal;  // streaming loads and stores (for copies too large to stay in the caches)
 };
 
 // Ring reduce-scatter arithmetic + 1/W scaling + all-gather for a range of tiles.
