@@ -24,7 +24,7 @@ struct ReduceTile {
   uint32_t pad_[3];
 };
 
-// One wavefront's share of pack / unpack: a run of one batch member.
+// One workgroup's share of pack / unpack: a run of one batch member.
 struct CopyTile {
   uint32_t row;        // tensor row
   uint32_t t_vec_off;  // offset inside the tensor, in vectors
@@ -50,7 +50,7 @@ struct TileShape {
   uint32_t long_vecs = 0;              // vectors per long tile; 0 (options only) = chosen at bind: 4096 or 8192
   uint32_t small_vecs = 256;           // vectors per small tile
   uint64_t long_run_bytes = 0;         // a run of at least this many bytes per replica is long; 0 (options only) = chosen at bind
-  uint32_t copy_vecs = 512;            // vectors per copy tile
+  uint32_t copy_vecs = 1024;           // vectors per copy tile: one per lane of the copy kernel's workgroup
   // Where every replica of a run has the same address modulo the tile size, the first tile of
   // the run is shortened so that all later ones start on multiples of the tile size in memory
   // (bit 0: small tiles, bit 1: long tiles).
