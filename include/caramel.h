@@ -346,7 +346,8 @@ enum {
   CARAMEL_OPT_SMALL_BLOCK = 10,
   /* Bytes per replica from which a run is cut into long tiles.  Default 0 = chosen at
    * caramel_bind: 16 KiB, or, if a replica holds less than 32 MiB in all, no long tiles at all
-   * (so small a job is over before the one-replica-at-a-time walk of a long tile pays off).
+   * (so small a job is over before the one-replica-at-a-time walk of a long tile pays off); none
+   * either for halving-doubling with more than 16 workers.
    * 1: every run is long; a huge value: every run is small. */
   CARAMEL_OPT_LONG_RUN_BYTES = 11,
   /* Long tiles: non-zero selects the stream-major kernel, which walks the workers one replica at
