@@ -320,7 +320,8 @@ enum {
   CARAMEL_OPT_BATCH_PATH = 1,
   /* 16-byte vectors per replica in a long tile.  Default 0 = chosen at caramel_bind: 8192
    * (128 KiB) for fp32 ring or shuffle sums over 2, 4 or 8 workers (the kernel can keep eight
-   * vectors per lane in registers then) once a replica holds 64 MiB; 4096 (64 KiB) otherwise. */
+   * vectors per lane in registers then) once a replica holds 64 MiB; 2048 (32 KiB) for bf16
+   * halving-doubling (two vectors per lane); 4096 (64 KiB) otherwise. */
   CARAMEL_OPT_TILE_VECS = 2,
   /* Upper bound on workgroups per reduce launch (0 = one workgroup per tile). */
   CARAMEL_OPT_MAX_GRID = 3,

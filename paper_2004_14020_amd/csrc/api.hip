@@ -799,7 +799,10 @@ void fill_binding(const caramel_plan* p, std::vector<uint64_t>&& rows, Binding& 
     const bool wide = c.dtype == CARAMEL_F32 && c.pattern != CARAMEL_PATTERN_HALVING_DOUBLING &&
                       (c.world == 2 || c.world == 4 || c.world == 8) && p->opt.stream_major >= 8 &&
                       p->opt.block == 1024 && replica_bytes >= (64u << 20);
-    bd.shape.long_vecs = wide ? 8192 : 4096;
+    // the bf16 tree keeps two vectors per lane: tiles of one pass (a second pass of a workgroup
+    // waits for the stores of the first; Transformer shapes 65.4 -> 66.5 %)
+    const bool narrow = c.dtype == CARAMEL_BF16 && c.pattern == CARAMEL_PATTERN_HALVING_DOUBLING;
+    bd.shape.long_vecs = wide ? 8192 : (narrow ? 2048 : 4096);
   }
   bd.rows = std::move(rows);
   build_tiles(p->host, bd.shape, bd.tt, bd.rows.data());
